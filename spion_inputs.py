@@ -1,0 +1,165 @@
+"""Seeded synthetic inputs for the SPION sparse-attention path.
+
+This module only *makes inputs*: Q, K, V, dO tensors and the head/batch-averaged dense
+attention-score map A^s with planted diagonal-band / vertical-stripe structure (the shapes the
+paper's motivation section reports for trained encoders: diagonal bands in early layers,
+vertical stripes in late layers).  It contains none of the method's arithmetic (no diagonal
+convolution, pooling, flood fill, compaction, sparse softmax or gradients) and imports neither
+the CPU oracle nor the HIP library, so both can be fed the same bytes.
+
+The five workloads are stand-ins for the paper's Long Range Arena runs (image L=1024 block 32,
+ListOps L=2048 block 64, retrieval L=4096 block 64, embedding size 64, filter 31x31; Section 5
+"Experimental Evaluation"); those datasets are not used here.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+T_ABS, T_QUANTILE, T_MEAN_KSTD = 0, 1, 2
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    cfg: int            # 1-based index into the benchmark's list of configurations
+    layer: int          # layer index inside a stack (0 for single-layer workloads)
+    B: int              # batch
+    H: int              # heads
+    L: int              # sequence length
+    d: int              # head dimension
+    dtype: str          # "f32" | "bf16"
+    block: int          # block size of the pooled / block-sparse pattern
+    band: int           # half-width of the planted diagonal band, in elements
+    n_stripes: int      # planted vertical stripes
+    stripe_w: int       # stripe width, in columns
+    n_offbands: int     # short off-diagonal bands (length 256, half-width 8)
+    filt: int           # diagonal filter size F (odd)
+    thresh_mode: int    # T_ABS | T_QUANTILE | T_MEAN_KSTD
+    thresh_value: float
+    seed: int
+    bias: float = 4.0   # logit bias added on the planted structure
+
+    @property
+    def nb(self) -> int:
+        return self.L // self.block
+
+
+def _wl(name, cfg, layer, B, H, L, dtype, block, band, ns, sw, nob, filt, tm, tv) -> Workload:
+    return Workload(name, cfg, layer, B, H, L, 64, dtype, block, band, ns, sw, nob, filt, tm, tv,
+                    seed=1000 * cfg + layer)
+
+
+# Configurations 1-4 and the four layers of configuration 5.
+WORKLOADS: List[Workload] = [
+    _wl("cfg1_tiny_f32_L256", 1, 0, 1, 1, 256, "f32", 16, 8, 3, 4, 0, 5, T_MEAN_KSTD, 1.0),
+    _wl("cfg2_bf16_L1024", 2, 0, 16, 4, 1024, "bf16", 32, 32, 8, 8, 0, 31, T_QUANTILE, 0.85),
+    _wl("cfg3_bf16_L2048", 3, 0, 8, 4, 2048, "bf16", 32, 48, 12, 8, 6, 31, T_QUANTILE, 0.90),
+    _wl("cfg4_bf16_L4096", 4, 0, 4, 4, 4096, "bf16", 64, 64, 16, 16, 0, 31, T_QUANTILE, 0.92),
+    _wl("cfg5_layer0", 5, 0, 4, 8, 4096, "bf16", 64, 32, 4, 16, 0, 31, T_QUANTILE, 0.96),
+    _wl("cfg5_layer1", 5, 1, 4, 8, 4096, "bf16", 64, 64, 10, 16, 0, 31, T_QUANTILE, 0.90),
+    _wl("cfg5_layer2", 5, 2, 4, 8, 4096, "bf16", 64, 128, 16, 16, 0, 31, T_QUANTILE, 0.83),
+    _wl("cfg5_layer3", 5, 3, 4, 8, 4096, "bf16", 64, 256, 24, 16, 0, 31, T_QUANTILE, 0.75),
+]
+
+
+def workload(name_or_cfg, layer: int = 0) -> Workload:
+    for w in WORKLOADS:
+        if w.name == name_or_cfg or (w.cfg == name_or_cfg and w.layer == layer):
+            return w
+    raise KeyError(name_or_cfg)
+
+
+# ----------------------------------------------------------------------------------------------
+# bf16 helpers (storage format only: round-to-nearest-even truncation of the fp32 bit pattern)
+# ----------------------------------------------------------------------------------------------
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 array -> uint16 array holding bf16 bit patterns (round to nearest, ties to even)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """uint16 bf16 bit patterns -> fp32 array with exactly those values."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def round_to_dtype(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Return an fp32 array whose values are exactly representable in `dtype`."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "f32":
+        return x
+    if dtype == "bf16":
+        return bf16_bits_to_f32(f32_to_bf16_bits(x))
+    raise ValueError(dtype)
+
+
+# ----------------------------------------------------------------------------------------------
+# generators
+# ----------------------------------------------------------------------------------------------
+def make_qkv_do(w: Workload, seed_offset: int = 0,
+                bh_limit: Optional[int] = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """Q, K, V, dO ~ N(0,1), shape [B*H (or bh_limit), L, d], fp32 holding values of w.dtype."""
+    rng = np.random.default_rng(w.seed + seed_offset)
+    bh = w.B * w.H
+    out = []
+    for _ in range(4):
+        t = rng.standard_normal((bh, w.L, w.d), dtype=np.float32)
+        out.append(round_to_dtype(t, w.dtype))
+    if bh_limit is not None:
+        out = [t[:bh_limit] for t in out]
+    return tuple(out)  # type: ignore[return-value]
+
+
+def structure_mask(w: Workload, seed_offset: int = 0) -> np.ndarray:
+    """0/1 fp32 [L, L]: union of the planted diagonal band, vertical stripes and short bands."""
+    rng = np.random.default_rng(w.seed + seed_offset + 7919)
+    L = w.L
+    i = np.arange(L)[:, None]
+    j = np.arange(L)[None, :]
+    M = (np.abs(i - j) <= w.band)
+    for _ in range(w.n_stripes):
+        c0 = int(rng.integers(0, L - w.stripe_w + 1))
+        M[:, c0:c0 + w.stripe_w] = True
+    for _ in range(w.n_offbands):
+        length, hw = 256, 8
+        while True:
+            r0 = int(rng.integers(0, L - length - hw))
+            c0 = int(rng.integers(0, L - length))
+            if abs(r0 - c0) >= 256:
+                break
+        for u in range(length):
+            lo = max(r0 + u - hw, 0)
+            hi = min(r0 + u + hw + 1, L)
+            M[lo:hi, c0 + u] = True
+    return M.astype(np.float32)
+
+
+def make_score_map(w: Workload, Q: np.ndarray, K: np.ndarray, seed_offset: int = 0) -> np.ndarray:
+    """A^s = mean over (batch, head) of softmax(Q K^T / sqrt(d) + bias * M), fp32 [L, L].
+
+    This is the product of the dense-attention phase that precedes pattern generation; it is an
+    input of the path under test, produced here with plain numpy.
+    """
+    M = structure_mask(w, seed_offset) * np.float32(w.bias)
+    acc = np.zeros((w.L, w.L), dtype=np.float32)
+    inv = np.float32(1.0 / np.sqrt(w.d))
+    for bh in range(Q.shape[0]):
+        S = (Q[bh] @ K[bh].T) * inv + M
+        S -= S.max(axis=1, keepdims=True)
+        np.exp(S, out=S)
+        S /= S.sum(axis=1, keepdims=True)
+        acc += S
+    acc /= np.float32(Q.shape[0])
+    return acc
+
+
+def random_block_mask(nb: int, density: float, seed: int) -> np.ndarray:
+    """uint8 [nb, nb] random block mask with the diagonal set (for attention-only tests)."""
+    rng = np.random.default_rng(seed)
+    m = (rng.random((nb, nb)) < density).astype(np.uint8)
+    m[np.arange(nb), np.arange(nb)] = 1
+    return m
