@@ -1,0 +1,150 @@
+/*
+ * spion.h - C ABI of the MI355X (gfx950) implementation of SPION's layer-wise sparse attention.
+ *
+ * Paper: "SPION: Layer-Wise Sparse Training of Transformer via Convolutional Flood Filling".
+ * The library covers the hot path of the method:
+ *   spion_pattern   - Algorithm 3 (generate_pattern): diagonal convolution (Eq. 3), average pooling
+ *                     (Eq. 4), flood fill (Algorithm 4) from the first-row and first-column seeds,
+ *                     forced diagonal, and the conversion of the pattern to a compressed index
+ *                     (Section 4.3; kept at block granularity as BSR plus its transpose BSC, since
+ *                     the upsampled pattern P is constant inside each B x B block).
+ *   spion_attn_fwd  - Algorithm 5 lines 4-7 / Eq. 5: SDDMM S = scale * Q K^T on the kept blocks, row
+ *                     softmax over the kept entries (Algorithm 6), SpMM O = P V; fused in one kernel.
+ *   spion_attn_bwd  - the gradient of Eq. 5 with respect to Q, K and V (Section 4.3, "Integration of
+ *                     GPU kernels with PyTorch", states that forward and backward kernels exist).
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says HOST.  The caller owns all buffers;
+ *     the library never allocates or frees device memory and keeps no state between calls.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the null stream) and
+ *     the call returns without synchronising.  Outputs are valid once the stream reaches that point.
+ *   - Return value: SPION_OK (0) or a negative spion_status.  Argument errors are detected on the
+ *     host before anything is enqueued; nothing is written in that case.
+ *   - Tensors Q, K, V, O, dO, dQ, dK, dV are [B, H, L, d] contiguous (d fastest) in the element type
+ *     named by `dtype`; LSE is fp32 [B, H, L].  Supported: d == 64, block in {16, 32, 64},
+ *     L % block == 0, L / block <= SPION_MAX_NB.
+ *   - One pattern (one BSR/BSC index) is shared by all batch items and heads of a layer.
+ */
+#ifndef SPION_H_
+#define SPION_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPION_MAX_NB 1024 /* largest supported number of block rows L / block */
+
+typedef enum {
+    SPION_OK = 0,
+    SPION_ERR_NULL = -1,      /* a required pointer is NULL */
+    SPION_ERR_SHAPE = -2,     /* unsupported L, d, block, B, H or nnzb */
+    SPION_ERR_DTYPE = -3,     /* dtype is not SPION_F32 / SPION_BF16 */
+    SPION_ERR_WORKSPACE = -4, /* workspace missing, misaligned (256 B) or too small */
+    SPION_ERR_PARAM = -5,     /* even filter, filter too large, quantile outside [0,1], bad flags */
+    SPION_ERR_HIP = -7        /* a HIP runtime call failed (launch error) */
+} spion_status;
+
+typedef enum { SPION_F32 = 0, SPION_BF16 = 1 } spion_dtype;
+
+/* How the flood-fill threshold t is derived from pool_out (Section 4.2 uses the alpha% quantile). */
+typedef enum {
+    SPION_T_ABS = 0,      /* thresh_value is t itself, in pool_out units */
+    SPION_T_QUANTILE = 1, /* thresh_value = q in [0,1]: t = sorted(pool_out)[floor(q*(n-1))], n = nb^2 */
+    SPION_T_MEAN_KSTD = 2 /* thresh_value = k: t = mean + k * population std of pool_out */
+} spion_thresh_mode;
+
+/* spion_pattern_params.flags */
+#define SPION_PATTERN_NO_FILL 1u /* SPION-C variant (Section 5): keep every block above t, no flood fill */
+
+typedef struct {
+    int32_t L;            /* sequence length */
+    int32_t block;        /* block size B of pooling / upsampling */
+    int32_t filter;       /* diagonal filter size F, odd, (F-1)/2 <= block; 1 = no convolution (SPION-F) */
+    int32_t thresh_mode;  /* spion_thresh_mode */
+    double thresh_value;  /* t, q or k, see spion_thresh_mode */
+    uint32_t flags;       /* SPION_PATTERN_* bits, otherwise 0 */
+    uint32_t reserved;    /* must be 0 */
+} spion_pattern_params;
+
+/* Bytes of device scratch spion_pattern needs for (L, block); 0 if the shape is unsupported. */
+size_t spion_pattern_workspace_bytes(int32_t L, int32_t block);
+
+/*
+ * Algorithm 3 on the GPU.
+ *   A_s       [L, L] fp32 row-major, the head/batch-averaged attention-score map; every entry must be
+ *             finite with |a| <= 1 (scores are quantised to 2^-40 fixed point so that the sums of
+ *             Eq. 3 and Eq. 4 are exact integers and the == / > tests of Algorithm 4 are exact).
+ *   p         HOST pointer to the parameters.
+ *   fl_out    [nb, nb] uint8, nb = L / block: the block-level pattern after the diagonal is forced.
+ *   row_ptr   [nb + 1], col_idx [capacity nb * nb; the first nnzb entries are written]: BSR index,
+ *             block rows in order, block columns ascending inside a row.
+ *   col_ptr   [nb + 1], row_idx [nb * nb], bsr_pos [nb * nb]: the transposed index (BSC), columns in
+ *             order, rows ascending; bsr_pos[k] is the position in col_idx of the k-th BSC entry.
+ *             The three may all be NULL if the caller needs no backward pass.
+ *   nnzb      device int32 scalar, number of kept blocks (== row_ptr[nb]).
+ *   pool_sum  optional [nb, nb] int64 output: block sums of the convolution output in fixed point,
+ *             pool_out = pool_sum / (block^2 * 2^40).  May be NULL.
+ *   workspace at least spion_pattern_workspace_bytes(L, block) bytes, 256-byte aligned.
+ */
+int spion_pattern(const float *A_s, const spion_pattern_params *p, uint8_t *fl_out, int32_t *row_ptr,
+                  int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx, int32_t *bsr_pos,
+                  int32_t *nnzb, int64_t *pool_sum, void *workspace, size_t workspace_bytes,
+                  void *hip_stream);
+
+/* spion_attn_params.flags */
+#define SPION_ATTN_PAPER_DENOM 1u /* add Algorithm 6's exp(-max) * (L - kept) term to the row sum */
+
+typedef struct {
+    int32_t B, H, L, d;  /* batch, heads, sequence length, head dimension (64) */
+    int32_t block;       /* block size of the pattern: 16, 32 or 64 */
+    int32_t dtype;       /* spion_dtype of Q, K, V, O, dO, dQ, dK, dV */
+    float scale;         /* score scale; 0 means 1 / sqrt(d) (Eq. 5) */
+    uint32_t flags;      /* SPION_ATTN_* bits, otherwise 0 */
+} spion_attn_params;
+
+/* Bytes of device scratch for the forward (is_bwd == 0) or backward (is_bwd != 0) call;
+ * (size_t)-1 if the parameters are unsupported. */
+size_t spion_attn_workspace_bytes(const spion_attn_params *p, int32_t nnzb, int32_t is_bwd);
+
+/*
+ * Eq. 5 on the kept blocks: for every (batch, head) and every block row I,
+ *   S_IJ = scale * Q_I K_J^T for J in the row's kept columns, P = softmax over the kept entries of
+ *   each row, O_I = sum_J P_IJ V_J, LSE_i = log sum_j exp(S_ij).
+ * A block row with no kept block gives O = 0 and LSE = -inf.
+ *   Q, K, V   inputs [B, H, L, d];  O output [B, H, L, d];  LSE output fp32 [B, H, L].
+ *   row_ptr, col_idx, nnzb  BSR index from spion_pattern (nnzb passed by value, as read back by the
+ *             caller); 0 <= col_idx < nb and row_ptr must be non-decreasing with row_ptr[nb] == nnzb.
+ *   p         HOST pointer.  workspace may be NULL when spion_attn_workspace_bytes(...) is 0.
+ */
+int spion_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                   const int32_t *row_ptr, const int32_t *col_idx, int32_t nnzb,
+                   const spion_attn_params *p, void *workspace, size_t workspace_bytes,
+                   void *hip_stream);
+
+/*
+ * Gradient of spion_attn_fwd:
+ *   delta_i = sum_c dO_ic O_ic;  P = exp(S - LSE);  dV_J += P^T dO_I;  dP = dO_I V_J^T;
+ *   dS = P .* (dP - delta);  dQ_I += scale * dS K_J;  dK_J += scale * dS^T Q_I.
+ *   Q, K, V, O, dO, LSE  as produced by / passed to spion_attn_fwd with the same index and params.
+ *   dQ, dK, dV  outputs [B, H, L, d]; overwritten (not accumulated).  Results are deterministic.
+ *   col_ptr, row_idx, bsr_pos  BSC index from spion_pattern (all required).
+ */
+int spion_attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                   const float *LSE, void *dQ, void *dK, void *dV, const int32_t *row_ptr,
+                   const int32_t *col_idx, const int32_t *col_ptr, const int32_t *row_idx,
+                   const int32_t *bsr_pos, int32_t nnzb, const spion_attn_params *p,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Static, NUL-terminated description of a spion_status value. */
+const char *spion_strerror(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int spion_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPION_H_ */

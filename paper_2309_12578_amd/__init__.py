@@ -1,0 +1,13 @@
+"""MI355X (gfx950) implementation of SPION's layer-wise sparse attention hot path.
+
+The product is the HIP library ``libspion.so`` (C ABI in ``include/spion.h``); this package is a
+thin ctypes binding around it plus the FLOP / byte accounting used by the benchmark.  There is no
+CPU fallback: every call fails loudly if the library is missing.
+"""
+from .binding import (  # noqa: F401
+    SPION_BF16, SPION_F32, SPION_T_ABS, SPION_T_MEAN_KSTD, SPION_T_QUANTILE,
+    SPION_PATTERN_NO_FILL, SPION_ATTN_PAPER_DENOM, SpionError, Pattern,
+    lib_path, load, spion_version, spion_strerror,
+    spion_pattern_workspace_bytes, spion_pattern, spion_attn_workspace_bytes,
+    spion_attn_fwd, spion_attn_bwd, generate_pattern, attn_fwd, attn_bwd,
+)

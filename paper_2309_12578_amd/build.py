@@ -1,0 +1,53 @@
+"""Build libspion.so (HIP, gfx950 only) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libspion.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+          # no compiler-generated packed-fp32 instructions
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# (source, extra flags).  The pattern kernels take threshold decisions in fp64 whose rounding must
+# follow the sequential definition: no fused multiply-add contraction there.
+SOURCES = [
+    ("spion_api.hip", ["-ffp-contract=off"]),
+    ("pattern_kernels.hip", ["-ffp-contract=off"]),
+    ("attn_kernels.hip", []),
+]
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source and link the shared library; always recompiles."""
+    objs = []
+
+    def compile_one(item):
+        src, extra = item
+        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        cmd = [HIPCC, *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        noise = "is not a recognized feature for this target"
+        err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed for {src}:\n{err}")
+        if verbose and err.strip():
+            print(err, file=sys.stderr)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+        objs = list(ex.map(compile_one, SOURCES))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link failed:\n" + res.stderr)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,183 @@
+// C ABI of libspion: argument validation, workspace carving and kernel launches.
+// Every entry point validates on the host, enqueues on the caller's stream and returns.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/spion.h"
+#include "spion_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool shape_ok(int32_t L, int32_t block) {
+    if (block != 16 && block != 32 && block != 64) return false;
+    if (L <= 0 || (L % block) != 0) return false;
+    return L / block <= SPION_MAX_NB;
+}
+
+// Layout of the pattern workspace for nb*nb = n cells.
+struct PatternWs {
+    size_t pool_off, mask_off, expd_off, pos_off, total;
+    explicit PatternWs(size_t n) {
+        pool_off = 0;
+        mask_off = pool_off + align_up(n * sizeof(int64_t));
+        expd_off = mask_off + align_up(n);
+        pos_off = expd_off + align_up(n);
+        total = pos_off + align_up(n * sizeof(int32_t));
+    }
+};
+
+int attn_params_ok(const spion_attn_params* p, int32_t nnzb) {
+    if (p->dtype != SPION_F32 && p->dtype != SPION_BF16) return SPION_ERR_DTYPE;
+    if (p->d != 64 || p->B <= 0 || p->H <= 0) return SPION_ERR_SHAPE;
+    if (!shape_ok(p->L, p->block)) return SPION_ERR_SHAPE;
+    const int64_t nb = p->L / p->block;
+    if ((int64_t)p->B * p->H * nb > 0x7fffffffll) return SPION_ERR_SHAPE;   // 1-D grid limit
+    if (nnzb < 0 || (int64_t)nnzb > nb * nb) return SPION_ERR_SHAPE;
+    if (!(p->scale >= 0.f) || !isfinite(p->scale)) return SPION_ERR_PARAM;
+    if (p->flags & ~SPION_ATTN_PAPER_DENOM) return SPION_ERR_PARAM;
+    return SPION_OK;
+}
+
+spion::AttnShape make_shape(const spion_attn_params* p) {
+    spion::AttnShape s;
+    s.BH = p->B * p->H;
+    s.L = p->L;
+    s.bs = p->block;
+    s.nb = p->L / p->block;
+    s.is_bf16 = p->dtype == SPION_BF16;
+    s.scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->d);
+    s.paper_denom = (p->flags & SPION_ATTN_PAPER_DENOM) ? 1 : 0;
+    return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spion_version(void) { return 100; }
+
+const char* spion_strerror(int status) {
+    switch (status) {
+        case SPION_OK: return "ok";
+        case SPION_ERR_NULL: return "a required pointer is NULL";
+        case SPION_ERR_SHAPE: return "unsupported shape (need d == 64, block in {16,32,64}, L % block == 0)";
+        case SPION_ERR_DTYPE: return "unsupported dtype";
+        case SPION_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case SPION_ERR_PARAM: return "invalid parameter value";
+        case SPION_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+size_t spion_pattern_workspace_bytes(int32_t L, int32_t block) {
+    if (!shape_ok(L, block)) return 0;
+    const size_t nb = (size_t)(L / block);
+    return PatternWs(nb * nb).total;
+}
+
+int spion_pattern(const float* A_s, const spion_pattern_params* p, uint8_t* fl_out, int32_t* row_ptr,
+                  int32_t* col_idx, int32_t* col_ptr, int32_t* row_idx, int32_t* bsr_pos, int32_t* nnzb,
+                  int64_t* pool_sum, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!A_s || !p || !fl_out || !row_ptr || !col_idx || !nnzb) return SPION_ERR_NULL;
+    const bool any_bsc = col_ptr || row_idx || bsr_pos;
+    if (any_bsc && !(col_ptr && row_idx && bsr_pos)) return SPION_ERR_NULL;
+    if (!shape_ok(p->L, p->block)) return SPION_ERR_SHAPE;
+    const int32_t bs = p->block, nb = p->L / bs;
+    if (p->filter < 1 || (p->filter % 2) == 0 || (p->filter - 1) / 2 > bs) return SPION_ERR_PARAM;
+    if (p->reserved != 0 || (p->flags & ~SPION_PATTERN_NO_FILL)) return SPION_ERR_PARAM;
+    const int64_t n = (int64_t)nb * nb;
+    int mode = 0;
+    long long k_rank = 0;
+    double kval = 0.0, t_abs = 0.0;
+    switch (p->thresh_mode) {
+        case SPION_T_ABS: {
+            if (!isfinite(p->thresh_value)) return SPION_ERR_PARAM;
+            const double cells = (double)bs * (double)bs;
+            const double scaled = p->thresh_value * cells;
+            t_abs = scaled * 1099511627776.0;   // pool_sum units: block^2 * 2^40
+            mode = 0;
+            break;
+        }
+        case SPION_T_QUANTILE: {
+            if (!(p->thresh_value >= 0.0 && p->thresh_value <= 1.0)) return SPION_ERR_PARAM;
+            k_rank = (long long)floor(p->thresh_value * (double)(n - 1));
+            if (k_rank < 0) k_rank = 0;
+            if (k_rank > n - 1) k_rank = n - 1;
+            mode = 1;
+            break;
+        }
+        case SPION_T_MEAN_KSTD:
+            if (!isfinite(p->thresh_value)) return SPION_ERR_PARAM;
+            kval = p->thresh_value;
+            mode = 2;
+            break;
+        default: return SPION_ERR_PARAM;
+    }
+    const PatternWs ws((size_t)n);
+    if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < ws.total)
+        return SPION_ERR_WORKSPACE;
+    char* w = static_cast<char*>(workspace);
+    long long* pool = pool_sum ? reinterpret_cast<long long*>(pool_sum)
+                               : reinterpret_cast<long long*>(w + ws.pool_off);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (spion::launch_conv_pool(A_s, p->L, bs, (p->filter - 1) / 2, pool, st) != hipSuccess)
+        return SPION_ERR_HIP;
+    if (spion::launch_pattern_finish(pool, nb, mode, k_rank, kval, t_abs,
+                                     (p->flags & SPION_PATTERN_NO_FILL) ? 1 : 0,
+                                     reinterpret_cast<uint8_t*>(w + ws.mask_off),
+                                     reinterpret_cast<uint8_t*>(w + ws.expd_off),
+                                     reinterpret_cast<int*>(w + ws.pos_off), fl_out, row_ptr, col_idx,
+                                     col_ptr, row_idx, bsr_pos, nnzb, st) != hipSuccess)
+        return SPION_ERR_HIP;
+    return SPION_OK;
+}
+
+size_t spion_attn_workspace_bytes(const spion_attn_params* p, int32_t nnzb, int32_t is_bwd) {
+    if (!p || attn_params_ok(p, nnzb) != SPION_OK) return (size_t)-1;
+    if (!is_bwd) return 0;
+    return align_up((size_t)p->B * p->H * p->L * sizeof(float));   // delta = rowsum(dO .* O)
+}
+
+int spion_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                   const int32_t* row_ptr, const int32_t* col_idx, int32_t nnzb,
+                   const spion_attn_params* p, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!Q || !K || !V || !O || !LSE || !row_ptr || !col_idx || !p) return SPION_ERR_NULL;
+    const int rc = attn_params_ok(p, nnzb);
+    if (rc != SPION_OK) return rc;
+    const spion::AttnShape s = make_shape(p);
+    if (spion::launch_attn_fwd(s, Q, K, V, O, LSE, row_ptr, col_idx,
+                               static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return SPION_ERR_HIP;
+    return SPION_OK;
+}
+
+int spion_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                   const float* LSE, void* dQ, void* dK, void* dV, const int32_t* row_ptr,
+                   const int32_t* col_idx, const int32_t* col_ptr, const int32_t* row_idx,
+                   const int32_t* bsr_pos, int32_t nnzb, const spion_attn_params* p, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !row_ptr || !col_idx || !col_ptr ||
+        !row_idx || !bsr_pos || !p)
+        return SPION_ERR_NULL;
+    const int rc = attn_params_ok(p, nnzb);
+    if (rc != SPION_OK) return rc;
+    const size_t need = spion_attn_workspace_bytes(p, nnzb, 1);
+    if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need)
+        return SPION_ERR_WORKSPACE;
+    const spion::AttnShape s = make_shape(p);
+    if (spion::launch_attn_bwd(s, Q, K, V, O, dO, LSE, dQ, dK, dV, row_ptr, col_idx, col_ptr, row_idx,
+                               static_cast<float*>(workspace),
+                               static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return SPION_ERR_HIP;
+    return SPION_OK;
+}
+
+}  // extern "C"

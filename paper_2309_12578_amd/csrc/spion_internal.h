@@ -1,0 +1,33 @@
+// Internal launcher declarations shared by the translation units of libspion (not installed).
+#ifndef SPION_INTERNAL_H_
+#define SPION_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spion {
+
+// pattern_kernels.hip
+hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* pool, hipStream_t st);
+hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long long k_rank, double kval,
+                                 double t_abs, int no_fill, uint8_t* mask, uint8_t* expd, int* pos,
+                                 uint8_t* fl, int* row_ptr, int* col_idx, int* col_ptr, int* row_idx,
+                                 int* bsr_pos, int* nnzb, hipStream_t st);
+
+// attn_kernels.hip
+struct AttnShape {
+    int BH, L, bs, nb;
+    int is_bf16;
+    float scale;        // resolved score scale (> 0)
+    int paper_denom;    // Algorithm 6's extra denominator term
+};
+
+hipError_t launch_attn_fwd(const AttnShape& s, const void* Q, const void* K, const void* V, void* O,
+                           float* LSE, const int* row_ptr, const int* col_idx, hipStream_t st);
+hipError_t launch_attn_bwd(const AttnShape& s, const void* Q, const void* K, const void* V,
+                           const void* O, const void* dO, const float* LSE, void* dQ, void* dK,
+                           void* dV, const int* row_ptr, const int* col_idx, const int* col_ptr,
+                           const int* row_idx, float* delta, hipStream_t st);
+
+}  // namespace spion
+#endif

@@ -1,0 +1,269 @@
+"""GPU parity: libspion (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: pattern outputs (pool_sum, fl_out, BSR, BSC, nnzb) bit-exact; attention outputs and
+gradients within 1e-5 (fp32) / 2e-2 (bf16), both as relative Frobenius error and as
+max|x - ref| / max|ref|, against the fp64 oracle fed the same (already rounded) input values.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import spion_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def sp():
+    import paper_2309_12578_amd as sp
+    sp.load()
+    return sp
+
+
+def _dev(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def _torch_dtype(name):
+    return torch.float32 if name == "f32" else torch.bfloat16
+
+
+def _rel_errors(x, ref):
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    fro = np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300)
+    mx = np.abs(x - ref).max() / max(np.abs(ref).max(), 1e-300)
+    return fro, mx
+
+
+def _check_pattern(sp, A, block, filt, mode, value, flags=0, variant="CF"):
+    ref = oracle.generate_pattern(A, block, filt, mode, value, variant=variant)
+    pat = sp.generate_pattern(_dev(A), block, filt, mode, value, flags=flags)
+    torch.cuda.synchronize()
+    n = ref["nnzb"]
+    assert np.array_equal(pat.pool_sum.cpu().numpy(), ref["pool_sum"]), "pool_sum"
+    assert np.array_equal(pat.fl_out.cpu().numpy(), ref["fl_out"]), "fl_out"
+    assert pat.nnzb == n
+    assert np.array_equal(pat.row_ptr.cpu().numpy(), ref["row_ptr"])
+    assert np.array_equal(pat.col_idx.cpu().numpy()[:n], ref["col_idx"])
+    assert np.array_equal(pat.col_ptr.cpu().numpy(), ref["col_ptr"])
+    assert np.array_equal(pat.row_idx.cpu().numpy()[:n], ref["row_idx"])
+    assert np.array_equal(pat.bsr_pos.cpu().numpy()[:n], ref["bsr_pos"])
+    return pat, ref
+
+
+# ------------------------------------------------------------------------------------------------
+# pattern
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", [w.name for w in si.WORKLOADS])
+def test_pattern_bit_exact_on_workloads(sp, name):
+    w = si.workload(name)
+    bh = min(w.B * w.H, 8)          # the averaged map of 8 heads has the same structure; keeps CPU time low
+    Q, K, _, _ = si.make_qkv_do(w, bh_limit=bh)
+    A = si.make_score_map(w, Q, K)
+    pat, ref = _check_pattern(sp, A, w.block, w.filt, w.thresh_mode, w.thresh_value)
+    dens = ref["nnzb"] / float(w.nb * w.nb)
+    print(f"{name}: nnzb={ref['nnzb']} density={dens:.4f}")
+    assert 0.0 < dens < 0.6
+
+
+@pytest.mark.parametrize("L,block,filt", [(64, 16, 1), (128, 16, 5), (256, 32, 31), (256, 64, 31),
+                                          (512, 32, 65), (2048, 16, 9), (192, 64, 129)])
+@pytest.mark.parametrize("mode,value", [(si.T_QUANTILE, 0.0), (si.T_QUANTILE, 0.7), (si.T_QUANTILE, 1.0),
+                                        (si.T_MEAN_KSTD, 0.5), (si.T_ABS, 0.02)])
+def test_pattern_bit_exact_on_random_maps_with_ties(sp, L, block, filt, mode, value):
+    rng = np.random.default_rng(L * 7 + block + filt)
+    # coarse values (multiples of 1/8 up to 1) make equal pooled sums and plateaus common
+    A = (rng.integers(0, 9, size=(L, L)) / 8.0).astype(np.float32)
+    A[rng.random((L, L)) < 0.5] = 0.0
+    if mode == si.T_ABS:
+        value = float(A.mean()) * filt * 1.1
+    _check_pattern(sp, A, block, filt, mode, value)
+
+
+def test_pattern_plateau_map_and_tiny_values(sp):
+    L, block = 128, 16
+    A = np.zeros((L, L), dtype=np.float32)        # every pooled value equal: all ties
+    _check_pattern(sp, A, block, 1, si.T_ABS, -1.0)     # everything reachable is above t
+    A[:] = 2.0 ** -41                               # rounds to 0 in fixed point (tie to even)
+    A[5, 7] = 3 * 2.0 ** -41                        # rounds to 2
+    A[9, 9] = -0.37
+    _check_pattern(sp, A, block, 3, si.T_QUANTILE, 0.5)
+
+
+def test_pattern_variants_no_fill_and_no_conv(sp):
+    w = si.workload(1)
+    Q, K, _, _ = si.make_qkv_do(w)
+    A = si.make_score_map(w, Q, K)
+    _check_pattern(sp, A, w.block, w.filt, si.T_QUANTILE, 0.9, flags=sp.SPION_PATTERN_NO_FILL, variant="C")
+    _check_pattern(sp, A, w.block, 1, si.T_QUANTILE, 0.9, variant="F")
+
+
+def test_pattern_is_deterministic_across_runs(sp):
+    w = si.workload(2)
+    Q, K, _, _ = si.make_qkv_do(w, bh_limit=4)
+    A = _dev(si.make_score_map(w, Q, K))
+    first = sp.generate_pattern(A, w.block, w.filt, w.thresh_mode, w.thresh_value)
+    for _ in range(5):
+        again = sp.generate_pattern(A, w.block, w.filt, w.thresh_mode, w.thresh_value)
+        assert torch.equal(first.fl_out, again.fl_out) and torch.equal(first.pool_sum, again.pool_sum)
+        assert torch.equal(first.col_idx[:first.nnzb], again.col_idx[:again.nnzb])
+
+
+# ------------------------------------------------------------------------------------------------
+# attention
+# ------------------------------------------------------------------------------------------------
+def _pattern_from_mask(sp, fl, block):
+    """Build the device index for a given block mask from the oracle's compaction (index bits are
+    themselves checked against spion_pattern in the tests above)."""
+    c = oracle.compact(fl)
+    nb = fl.shape[0]
+    pad = np.zeros(nb * nb, dtype=np.int32)
+
+    def full(a):
+        out = pad.copy()
+        out[:a.size] = a
+        return out
+
+    return sp.Pattern(nb * block, block, _dev(fl), _dev(c["row_ptr"]), _dev(full(c["col_idx"])),
+                      _dev(c["col_ptr"]), _dev(full(c["row_idx"])), _dev(full(c["bsr_pos"])),
+                      _dev(np.array([c["nnzb"]], dtype=np.int32)),
+                      torch.zeros((nb, nb), dtype=torch.int64, device="cuda"), c["nnzb"])
+
+
+def _run_attention_case(sp, Q, K, V, dO, fl, block, dtype, flags=0, heads=None, scale=0.0):
+    """Q.. are fp32 numpy [BH, L, d] holding values exactly representable in dtype."""
+    BH, L, d = Q.shape
+    tdt = _torch_dtype(dtype)
+    pat = _pattern_from_mask(sp, fl, block)
+    q, k, v, do = [_dev(t, tdt).view(1, BH, L, d) for t in (Q, K, V, dO)]
+    O, LSE = sp.attn_fwd(q, k, v, pat, scale=scale, flags=flags)
+    dQ, dK, dV = sp.attn_bwd(q, k, v, O, do, LSE, pat, scale=scale, flags=flags)
+    torch.cuda.synchronize()
+    sel = list(range(BH)) if heads is None else heads
+    P = oracle.upsample(fl, block)
+    sc = None if scale == 0.0 else scale
+    oflags = oracle.ATTN_PAPER_DENOM if flags & sp.SPION_ATTN_PAPER_DENOM else 0
+    rO, rLSE = oracle.attn_fwd(Q[sel], K[sel], V[sel], P, scale=sc, flags=oflags)
+    rdQ, rdK, rdV = oracle.attn_bwd(Q[sel], K[sel], V[sel], dO[sel], P, scale=sc, flags=oflags)
+    tol = TOL[dtype]
+    got = {"O": O, "dQ": dQ, "dK": dK, "dV": dV}
+    ref = {"O": rO, "dQ": rdQ, "dK": rdK, "dV": rdV}
+    errs = {}
+    for name in got:
+        x = got[name].float().cpu().numpy().reshape(BH, L, d)[sel]
+        assert np.all(np.isfinite(x)), name
+        errs[name] = _rel_errors(x, ref[name])
+    lse = LSE.cpu().numpy().reshape(BH, L)[sel]
+    fin = np.isfinite(rLSE)
+    assert np.array_equal(np.isneginf(lse), np.isneginf(rLSE))
+    errs["LSE"] = (np.abs(lse[fin] - rLSE[fin]).max() / max(np.abs(rLSE[fin]).max(), 1.0),) * 2
+    for name, (fro, mx) in errs.items():
+        assert fro <= tol and mx <= tol, (name, fro, mx, tol)
+    return errs
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("block", [16, 32, 64])
+@pytest.mark.parametrize("density", [1.0, 0.3])
+def test_attention_small_all_kernels(sp, dtype, block, density):
+    nb, BH, d = 5, 3, 64          # several tiles per row plus ragged row/column lengths
+    L = nb * block
+    rng = np.random.default_rng(block * 10 + int(density * 10))
+    Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), dtype)
+                   for _ in range(4)]
+    fl = si.random_block_mask(nb, density, seed=block)
+    errs = _run_attention_case(sp, Q, K, V, dO, fl, block, dtype)
+    print(dtype, block, density, {k: f"{v[0]:.2e}" for k, v in errs.items()})
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attention_degenerate_patterns(sp, dtype):
+    block, nb, BH, d = 32, 4, 2, 64
+    L = nb * block
+    rng = np.random.default_rng(3)
+    Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), dtype)
+                   for _ in range(4)]
+    diag = np.eye(nb, dtype=np.uint8)                       # one block per row and column
+    _run_attention_case(sp, Q, K, V, dO, diag, block, dtype)
+    stripe = np.eye(nb, dtype=np.uint8)
+    stripe[:, 2] = 1                                         # one full column: longest column walk
+    stripe[1, :] = 1                                         # one full row
+    _run_attention_case(sp, Q, K, V, dO, stripe, block, dtype)
+    empty_row = np.ones((nb, nb), dtype=np.uint8)
+    empty_row[2, :] = 0                                      # a block row with no kept block
+    _run_attention_case(sp, Q, K, V, dO, empty_row, block, dtype)
+    one = np.ones((1, 1), dtype=np.uint8)                    # smallest problem: L == block
+    _run_attention_case(sp, Q[:, :block], K[:, :block], V[:, :block], dO[:, :block], one, block, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attention_paper_denominator_and_explicit_scale(sp, dtype):
+    block, nb, BH, d = 16, 6, 2, 64
+    L = nb * block
+    rng = np.random.default_rng(4)
+    Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), dtype)
+                   for _ in range(4)]
+    fl = si.random_block_mask(nb, 0.4, seed=9)
+    _run_attention_case(sp, Q, K, V, dO, fl, block, dtype, flags=sp.SPION_ATTN_PAPER_DENOM)
+    _run_attention_case(sp, Q, K, V, dO, fl, block, dtype, scale=0.2)
+
+
+def test_attention_large_scores_stay_finite(sp):
+    block, nb, BH, d = 32, 3, 1, 64
+    L = nb * block
+    rng = np.random.default_rng(5)
+    Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32) * s, "bf16")
+                   for s in (6.0, 6.0, 1.0, 1.0)]          # scores of a few hundred
+    fl = si.random_block_mask(nb, 0.6, seed=1)
+    _run_attention_case(sp, Q, K, V, dO, fl, block, "bf16")
+
+
+@pytest.mark.parametrize("name,heads", [("cfg1_tiny_f32_L256", None), ("cfg2_bf16_L1024", 16),
+                                        ("cfg3_bf16_L2048", 8), ("cfg4_bf16_L4096", 4),
+                                        ("cfg5_layer0", 2), ("cfg5_layer3", 2)])
+def test_attention_workloads_full_size(sp, name, heads):
+    """Full-size launch (all batch items and heads, the configuration the benchmark times) with the
+    pattern produced by spion_pattern; the oracle checks a spread of (batch, head) slices."""
+    w = si.workload(name)
+    Q, K, V, dO = si.make_qkv_do(w)
+    A = si.make_score_map(w, Q[:8], K[:8])
+    pat = sp.generate_pattern(_dev(A), w.block, w.filt, w.thresh_mode, w.thresh_value)
+    fl = pat.fl_out.cpu().numpy()
+    assert np.array_equal(fl, oracle.generate_pattern(A, w.block, w.filt, w.thresh_mode, w.thresh_value)["fl_out"])
+    BH = w.B * w.H
+    sel = None if heads is None else sorted(set(np.linspace(0, BH - 1, heads).astype(int).tolist()))
+    errs = _run_attention_case(sp, Q, K, V, dO, fl, w.block, w.dtype, heads=sel)
+    print(name, f"nnzb={pat.nnzb}", {k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in errs.items()})
+
+
+def test_attention_backward_is_deterministic(sp):
+    w = si.workload(2)
+    Q, K, V, dO = si.make_qkv_do(w, bh_limit=8)
+    fl = si.random_block_mask(w.nb, 0.2, seed=2)
+    fl[:, 3] = 1
+    pat = _pattern_from_mask(sp, fl, w.block)
+    q, k, v, do = [_dev(t, torch.bfloat16).view(2, 4, w.L, w.d) for t in (Q, K, V, dO)]
+    O, LSE = sp.attn_fwd(q, k, v, pat)
+    first = [t.clone() for t in sp.attn_bwd(q, k, v, O, do, LSE, pat)]
+    for _ in range(3):
+        again = sp.attn_bwd(q, k, v, O, do, LSE, pat)
+        for a, b in zip(first, again):
+            assert torch.equal(a, b)
+
+
+def test_error_codes_need_no_launch(sp):
+    A = torch.zeros((64, 64), device="cuda")
+    with pytest.raises(sp.SpionError) as e:
+        sp.generate_pattern(A, 16, 4, si.T_QUANTILE, 0.5)          # even filter
+    assert e.value.code == -5
+    with pytest.raises(sp.SpionError) as e:
+        sp.generate_pattern(A, 24, 5, si.T_QUANTILE, 0.5)          # unsupported block
+    assert e.value.code == -2
+    with pytest.raises(sp.SpionError) as e:
+        sp.generate_pattern(A, 16, 5, si.T_QUANTILE, 1.5)          # quantile outside [0, 1]
+    assert e.value.code == -5
