@@ -6,7 +6,8 @@ CPU fallback: every call fails loudly if the library is missing.
 """
 from .binding import (  # noqa: F401
     SPION_BF16, SPION_F32, SPION_T_ABS, SPION_T_MEAN_KSTD, SPION_T_QUANTILE,
-    SPION_PATTERN_NO_FILL, SPION_ATTN_PAPER_DENOM, SpionError, Pattern,
+    SPION_PATTERN_NO_FILL, SPION_ATTN_PAPER_DENOM, SPION_ATTN_BWD_QUERY_SIDE_ONLY,
+    SPION_ATTN_BWD_KEY_SIDE_ONLY, SpionError, Pattern,
     lib_path, load, spion_version, spion_strerror,
     spion_pattern_workspace_bytes, spion_pattern, spion_attn_workspace_bytes,
     spion_attn_fwd, spion_attn_bwd, generate_pattern, attn_fwd, attn_bwd,

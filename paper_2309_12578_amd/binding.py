@@ -19,6 +19,8 @@ SPION_F32, SPION_BF16 = 0, 1
 SPION_T_ABS, SPION_T_QUANTILE, SPION_T_MEAN_KSTD = 0, 1, 2
 SPION_PATTERN_NO_FILL = 1
 SPION_ATTN_PAPER_DENOM = 1
+SPION_ATTN_BWD_QUERY_SIDE_ONLY = 2
+SPION_ATTN_BWD_KEY_SIDE_ONLY = 4
 
 
 class SpionError(RuntimeError):

@@ -412,16 +412,20 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
                         const int* row_ptr, const int* col_idx, const int* col_ptr, const int* row_idx,
                         float* delta, hipStream_t st) {
     const dim3 grid((unsigned)(s.nb * s.BH)), block(BS * 4);
-    attn_bwd_dq_kernel<T, BS><<<grid, block, 0, st>>>(
-        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-        static_cast<const T*>(O), static_cast<const T*>(dO), LSE, static_cast<T*>(dQ), delta, row_ptr,
-        col_idx, s.L, s.nb, s.scale, s.scale * kLog2e);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    attn_bwd_dkv_kernel<T, BS><<<grid, block, 0, st>>>(
-        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-        static_cast<const T*>(dO), LSE, delta, static_cast<T*>(dK), static_cast<T*>(dV), col_ptr,
-        row_idx, s.L, s.nb, s.scale, s.scale * kLog2e);
+    if (s.bwd_phases & 1) {
+        attn_bwd_dq_kernel<T, BS><<<grid, block, 0, st>>>(
+            static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+            static_cast<const T*>(O), static_cast<const T*>(dO), LSE, static_cast<T*>(dQ), delta,
+            row_ptr, col_idx, s.L, s.nb, s.scale, s.scale * kLog2e);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (s.bwd_phases & 2) {
+        attn_bwd_dkv_kernel<T, BS><<<grid, block, 0, st>>>(
+            static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+            static_cast<const T*>(dO), LSE, delta, static_cast<T*>(dK), static_cast<T*>(dV), col_ptr,
+            row_idx, s.L, s.nb, s.scale, s.scale * kLog2e);
+    }
     return hipGetLastError();
 }
 

@@ -39,7 +39,10 @@ int attn_params_ok(const spion_attn_params* p, int32_t nnzb) {
     if ((int64_t)p->B * p->H * nb > 0x7fffffffll) return SPION_ERR_SHAPE;   // 1-D grid limit
     if (nnzb < 0 || (int64_t)nnzb > nb * nb) return SPION_ERR_SHAPE;
     if (!(p->scale >= 0.f) || !isfinite(p->scale)) return SPION_ERR_PARAM;
-    if (p->flags & ~SPION_ATTN_PAPER_DENOM) return SPION_ERR_PARAM;
+    const uint32_t known = SPION_ATTN_PAPER_DENOM | SPION_ATTN_BWD_QUERY_SIDE_ONLY | SPION_ATTN_BWD_KEY_SIDE_ONLY;
+    if (p->flags & ~known) return SPION_ERR_PARAM;
+    if ((p->flags & SPION_ATTN_BWD_QUERY_SIDE_ONLY) && (p->flags & SPION_ATTN_BWD_KEY_SIDE_ONLY))
+        return SPION_ERR_PARAM;
     return SPION_OK;
 }
 
@@ -52,6 +55,8 @@ spion::AttnShape make_shape(const spion_attn_params* p) {
     s.is_bf16 = p->dtype == SPION_BF16;
     s.scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->d);
     s.paper_denom = (p->flags & SPION_ATTN_PAPER_DENOM) ? 1 : 0;
+    s.bwd_phases = (p->flags & SPION_ATTN_BWD_QUERY_SIDE_ONLY) ? 1
+                   : (p->flags & SPION_ATTN_BWD_KEY_SIDE_ONLY) ? 2 : 3;
     return s;
 }
 

@@ -20,6 +20,7 @@ struct AttnShape {
     int is_bf16;
     float scale;        // resolved score scale (> 0)
     int paper_denom;    // Algorithm 6's extra denominator term
+    int bwd_phases;     // bit 0: query-side kernel (delta, dQ); bit 1: key-side kernel (dK, dV)
 };
 
 hipError_t launch_attn_fwd(const AttnShape& s, const void* Q, const void* K, const void* V, void* O,
