@@ -62,7 +62,7 @@ typedef enum {
 typedef struct {
     int32_t L;            /* sequence length */
     int32_t block;        /* block size B of pooling / upsampling */
-    int32_t filter;       /* diagonal filter size F, odd, (F-1)/2 <= block; 1 = no convolution (SPION-F) */
+    int32_t filter;       /* diagonal filter size F, odd, (F-1)/2 < block; 1 = no convolution (SPION-F) */
     int32_t thresh_mode;  /* spion_thresh_mode */
     double thresh_value;  /* t, q or k, see spion_thresh_mode */
     uint32_t flags;       /* SPION_PATTERN_* bits, otherwise 0 */

@@ -239,6 +239,55 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
+// Key-side work list.  Vertical stripes give block columns with up to nb kept rows next to columns
+// with one or two, so the key-side kernel does not take one column per workgroup: a column with cnt
+// kept rows is cut into nch = ceil(cnt / kChunk) near-equal chunks, each a work item.  A column with
+// one chunk writes dK / dV directly; the chunks of a longer column write fp32 partial tiles into
+// numbered slots that a second kernel adds up in chunk order (deterministic).  The list is the same
+// for every head; one wave of the query-side kernel (which always runs first) builds it.
+//   sched[w]   = {J, kb, ke, slot}: BSC entries [kb, ke) of column J; slot < 0: write final output;
+//                J < 0: unused work item
+//   colinfo[J] = {first slot, nch}
+// ------------------------------------------------------------------------------------------------
+constexpr int kChunk = 8;
+
+__host__ __device__ inline int key_work_items_max(int nnzb, int nb) { return nnzb / kChunk + nb; }
+__host__ __device__ inline int key_slots_max(int nnzb) { return 2 * (nnzb / kChunk) + 2; }
+
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(v, off);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+__device__ void build_key_schedule(const int* __restrict__ col_ptr, int nb, int w_max,
+                                   int4* __restrict__ sched, int2* __restrict__ colinfo, int lane) {
+    int run_w = 0, run_s = 0;
+    for (int base = 0; base < nb; base += 64) {
+        const int J = base + lane;
+        const bool valid = J < nb;
+        const int c0 = valid ? col_ptr[J] : 0;
+        const int cnt = valid ? col_ptr[J + 1] - c0 : 0;
+        const int nch = valid ? (cnt > kChunk ? (cnt + kChunk - 1) / kChunk : 1) : 0;
+        const int ns = nch > 1 ? nch : 0;
+        const int w_incl = wave_incl_scan(nch, lane), s_incl = wave_incl_scan(ns, lane);
+        const int w0 = run_w + w_incl - nch, s0 = run_s + s_incl - ns;
+        if (valid) {
+            colinfo[J] = make_int2(nch > 1 ? s0 : -1, nch);
+            for (int ci = 0; ci < nch && w0 + ci < w_max; ++ci)
+                sched[w0 + ci] = make_int4(J, c0 + (ci * cnt) / nch, c0 + ((ci + 1) * cnt) / nch,
+                                           nch > 1 ? s0 + ci : -1);
+        }
+        run_w += __shfl(w_incl, 63);
+        run_s += __shfl(s_incl, 63);
+    }
+    for (int w = run_w + lane; w < w_max; w += 64) sched[w] = make_int4(-1, 0, 0, -1);
+}
+
+// ------------------------------------------------------------------------------------------------
 // backward, query side: workgroup = (head, block row I).  Computes delta = rowsum(dO .* O) for its
 // rows (stored for the key-side kernel) and dQ.
 // ------------------------------------------------------------------------------------------------
@@ -247,7 +296,10 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ O,
     const T* __restrict__ dO, const float* __restrict__ LSE, T* __restrict__ dQ,
     float* __restrict__ delta_out, const int* __restrict__ row_ptr, const int* __restrict__ col_idx,
+    const int* __restrict__ col_ptr, int w_max, int4* __restrict__ sched, int2* __restrict__ colinfo,
     int L, int nb, float scale, float scale_log2) {
+    if (blockIdx.x == 0 && threadIdx.x < 64)
+        build_key_schedule(col_ptr, nb, w_max, sched, colinfo, threadIdx.x);
     typedef typename Elem<T>::Frag Frag;
     typedef typename Elem<T>::Quad Quad;
     constexpr int EPL = Elem<T>::EPL, KC = Elem<T>::KC, NDC = kD / KC, NKT = BS / 16;
@@ -313,15 +365,16 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward, key side: workgroup = (head, block column J); wave w owns keys J*bs + 16 w .. + 15 and
-// walks the kept rows of the column (BSC).  Deterministic: no atomics, one writer per output.
+// backward, key side: workgroup = (head, work item w) with sched[w] = a chunk of the kept rows of
+// block column J; wave w owns keys J*bs + 16 w .. + 15.  Deterministic: no atomics, one writer per
+// output or per partial slot.
 // ------------------------------------------------------------------------------------------------
 template <typename T, int BS>
 __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ dO,
     const float* __restrict__ LSE, const float* __restrict__ delta, T* __restrict__ dK,
-    T* __restrict__ dV, const int* __restrict__ col_ptr, const int* __restrict__ row_idx, int L, int nb,
-    float scale, float scale_log2) {
+    T* __restrict__ dV, const int* __restrict__ row_idx, const int4* __restrict__ sched, int w_max,
+    int n_slots, float* __restrict__ partial, int L, float scale, float scale_log2) {
     typedef typename Elem<T>::Frag Frag;
     typedef typename Elem<T>::Quad Quad;
     constexpr int EPL = Elem<T>::EPL, KC = Elem<T>::KC, NDC = kD / KC, NQT = BS / 16;
@@ -332,7 +385,10 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_kernel(
     __shared__ __attribute__((aligned(16))) T do_tr[kD * LDT];
     __shared__ float lse_s[BS], delta_s[BS];
 
-    const int J = blockIdx.x % nb, bh = blockIdx.x / nb;
+    const int w = blockIdx.x % w_max, bh = blockIdx.x / w_max;
+    const int4 item = sched[w];
+    const int J = item.x, kb = item.y, ke = item.z, slot = item.w;
+    if (J < 0) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     const size_t head = (size_t)bh * L * kD;
     const int krow = J * BS + wave * 16 + r;
@@ -351,7 +407,6 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_kernel(
         dv[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const int kb = col_ptr[J], ke = col_ptr[J + 1];
     for (int k = kb; k < ke; ++k) {
         const int I = row_idx[k];
         __syncthreads();
@@ -385,18 +440,69 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_kernel(
         mma_over_rows<T, BS, LDT>(dv, do_tr, pq, r, g);   // dV^T[d][key] += dO^T P
         mma_over_rows<T, BS, LDT>(dk, q_tr, dsq, r, g);   // dK^T[d][key] += Q^T dS
     }
-    T* dkrow = dK + head + (size_t)krow * kD;
-    T* dvrow = dV + head + (size_t)krow * kD;
+    if (slot < 0) {
+        T* dkrow = dK + head + (size_t)krow * kD;
+        T* dvrow = dV + head + (size_t)krow * kD;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-        store_quad<T>(dkrow + dt * 16 + 4 * g, dk[dt] * scale);
-        store_quad<T>(dvrow + dt * 16 + 4 * g, dv[dt]);
+        for (int dt = 0; dt < 4; ++dt) {
+            store_quad<T>(dkrow + dt * 16 + 4 * g, dk[dt] * scale);
+            store_quad<T>(dvrow + dt * 16 + 4 * g, dv[dt]);
+        }
+    } else {
+        // fp32 partial tiles [head][slot][dK | dV][bs][64], unscaled
+        float* pk = partial + ((size_t)bh * n_slots + slot) * (2 * BS * kD) + (size_t)(wave * 16 + r) * kD;
+        float* pv = pk + BS * kD;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            *reinterpret_cast<f32x4*>(pk + dt * 16 + 4 * g) = dk[dt];
+            *reinterpret_cast<f32x4*>(pv + dt * 16 + 4 * g) = dv[dt];
+        }
+    }
+}
+
+// Adds the partial tiles of every block column that was cut into several chunks, in chunk order.
+// workgroup = (head, block column J); thread t owns float4 number t, t + NT, ... of the tile.
+template <typename T, int BS>
+__global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_reduce_kernel(
+    const float* __restrict__ partial, const int2* __restrict__ colinfo, int n_slots, T* __restrict__ dK,
+    T* __restrict__ dV, int L, int nb, float scale) {
+    const int J = blockIdx.x % nb, bh = blockIdx.x / nb;
+    const int2 info = colinfo[J];
+    if (info.y <= 1) return;
+    constexpr int NT = BS * 4, NV = BS * kD / 4;
+    const float* base = partial + ((size_t)bh * n_slots + info.x) * (2 * BS * kD);
+    const size_t out0 = (size_t)bh * L * kD + (size_t)J * BS * kD;
+    for (int v = threadIdx.x; v < NV; v += NT) {
+        f32x4 ak = f32x4{0.f, 0.f, 0.f, 0.f}, av = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < info.y; ++c) {
+            const float* pk = base + (size_t)c * (2 * BS * kD);
+            ak += *reinterpret_cast<const f32x4*>(pk + v * 4);
+            av += *reinterpret_cast<const f32x4*>(pk + BS * kD + v * 4);
+        }
+        store_quad<T>(dK + out0 + v * 4, ak * scale);
+        store_quad<T>(dV + out0 + v * 4, av);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // host launchers
 // ------------------------------------------------------------------------------------------------
+size_t attn_bwd_workspace_bytes(int BH, int L, int bs, int nb, int nnzb) {
+    const BwdWorkspace ws(BH, L, bs, nb, nnzb);
+    return ws.total;
+}
+
+BwdWorkspace::BwdWorkspace(int BH, int L, int bs, int nb, int nnzb) {
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    w_max = key_work_items_max(nnzb, nb);
+    n_slots = key_slots_max(nnzb);
+    delta_off = 0;
+    sched_off = delta_off + up((size_t)BH * L * sizeof(float));
+    colinfo_off = sched_off + up((size_t)w_max * sizeof(int4));
+    partial_off = colinfo_off + up((size_t)nb * sizeof(int2));
+    total = partial_off + up((size_t)BH * n_slots * 2 * bs * kD * sizeof(float));
+}
+
 template <typename T, int BS>
 static hipError_t fwd_t(const AttnShape& s, const void* Q, const void* K, const void* V, void* O,
                         float* LSE, const int* row_ptr, const int* col_idx, hipStream_t st) {
@@ -410,21 +516,31 @@ template <typename T, int BS>
 static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
                         const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
                         const int* row_ptr, const int* col_idx, const int* col_ptr, const int* row_idx,
-                        float* delta, hipStream_t st) {
-    const dim3 grid((unsigned)(s.nb * s.BH)), block(BS * 4);
+                        int nnzb, void* workspace, hipStream_t st) {
+    const BwdWorkspace ws(s.BH, s.L, s.bs, s.nb, nnzb);
+    char* base = static_cast<char*>(workspace);
+    float* delta = reinterpret_cast<float*>(base + ws.delta_off);
+    int4* sched = reinterpret_cast<int4*>(base + ws.sched_off);
+    int2* colinfo = reinterpret_cast<int2*>(base + ws.colinfo_off);
+    float* partial = reinterpret_cast<float*>(base + ws.partial_off);
+    const dim3 block(BS * 4);
     if (s.bwd_phases & 1) {
-        attn_bwd_dq_kernel<T, BS><<<grid, block, 0, st>>>(
+        attn_bwd_dq_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
             static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
             static_cast<const T*>(O), static_cast<const T*>(dO), LSE, static_cast<T*>(dQ), delta,
-            row_ptr, col_idx, s.L, s.nb, s.scale, s.scale * kLog2e);
+            row_ptr, col_idx, col_ptr, ws.w_max, sched, colinfo, s.L, s.nb, s.scale, s.scale * kLog2e);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (s.bwd_phases & 2) {
-        attn_bwd_dkv_kernel<T, BS><<<grid, block, 0, st>>>(
+        attn_bwd_dkv_kernel<T, BS><<<dim3((unsigned)(ws.w_max * s.BH)), block, 0, st>>>(
             static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-            static_cast<const T*>(dO), LSE, delta, static_cast<T*>(dK), static_cast<T*>(dV), col_ptr,
-            row_idx, s.L, s.nb, s.scale, s.scale * kLog2e);
+            static_cast<const T*>(dO), LSE, delta, static_cast<T*>(dK), static_cast<T*>(dV), row_idx,
+            sched, ws.w_max, ws.n_slots, partial, s.L, s.scale, s.scale * kLog2e);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        attn_bwd_dkv_reduce_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
+            partial, colinfo, ws.n_slots, static_cast<T*>(dK), static_cast<T*>(dV), s.L, s.nb, s.scale);
     }
     return hipGetLastError();
 }
@@ -449,9 +565,9 @@ hipError_t launch_attn_fwd(const AttnShape& s, const void* Q, const void* K, con
 hipError_t launch_attn_bwd(const AttnShape& s, const void* Q, const void* K, const void* V,
                            const void* O, const void* dO, const float* LSE, void* dQ, void* dK,
                            void* dV, const int* row_ptr, const int* col_idx, const int* col_ptr,
-                           const int* row_idx, float* delta, hipStream_t st) {
-    SPION_DISPATCH(bwd_t, s, Q, K, V, O, dO, LSE, dQ, dK, dV, row_ptr, col_idx, col_ptr, row_idx, delta,
-                   st);
+                           const int* row_idx, int nnzb, void* workspace, hipStream_t st) {
+    SPION_DISPATCH(bwd_t, s, Q, K, V, O, dO, LSE, dQ, dK, dV, row_ptr, col_idx, col_ptr, row_idx, nnzb,
+                   workspace, st);
 }
 
 }  // namespace spion

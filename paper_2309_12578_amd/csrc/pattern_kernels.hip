@@ -7,9 +7,9 @@
 //                         successor bits, anti-diagonal wavefront flood fill, forced diagonal,
 //                         BSR + BSC compaction.  Latency bound (nb^2 <= ~1M cells).
 //
-// Arithmetic: a_q = rint(a * 2^40) in int64; all sums are integer, so any summation order (tiling,
-// atomics) gives the same bits.  This file is compiled with -ffp-contract=off: the fp64 mean / std
-// threshold must round exactly as its sequential definition.
+// Arithmetic: a_q = rint(a * 2^40) as an exact integer; all sums are integer, so any summation
+// order (tiling, atomics) gives the same bits.  This file is compiled with -ffp-contract=off: the
+// fp64 mean / std threshold must round exactly as its sequential definition.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -22,13 +22,20 @@ namespace spion {
 // ------------------------------------------------------------------------------------------------
 // Input block (I, J) of A^s (bs x bs scores).  conv_out(i, j) = sum_{g=-p..p} a(i+g, j+g), so the
 // score at local position (u, v) of this block is added to the outputs (u-g, v-g), g in [-p, p].
-// Those outputs fall into blocks (I+di, J+dj) with di, dj in {-1, 0, +1} (p <= bs) and never into
+// Those outputs fall into blocks (I+di, J+dj) with di, dj in {-1, 0, +1} (p < bs) and never into
 // (-1,+1) or (+1,-1) because g shifts both coordinates alike.  The number of g landing in
-// (di, dj) is the size of an interval intersection, a small integer weight; the block
-// contributes sum(weight * a_q) to each of its 7 possible targets.
+// (di, dj) is the size of an interval intersection, a small integer weight w(di, dj); the seven
+// weights of an element add up to F.  Hence
+//     contribution to a neighbour block = sum w * a_q          (only near the block's edges)
+//     contribution to (I, J) itself     = F * sum a_q - (sum of the six neighbour contributions)
+// and elements at least p away from every edge cost one addition.
 //
 // g-intervals for a local coordinate x in [0, bs): block offset -1: [x+1, p], 0: [max(x-bs+1,-p),
 // min(x,p)], +1: [-p, x-bs].
+//
+// Fixed point without 64-bit arithmetic in the inner loop: for |a| <= 1, x = a * 2^20 is exact in
+// fp32, hi = floor(x), lo = rint((x - hi) * 2^20) are exact integers of at most 21 bits and
+// a_q = hi * 2^20 + lo == rint(a * 2^40) with ties to even.
 __device__ __forceinline__ int isect(int lo_a, int hi_a, int lo_b, int hi_b) {
     const int lo = lo_a > lo_b ? lo_a : lo_b;
     const int hi = hi_a < hi_b ? hi_a : hi_b;
@@ -36,68 +43,132 @@ __device__ __forceinline__ int isect(int lo_a, int hi_a, int lo_b, int hi_b) {
     return n > 0 ? n : 0;
 }
 
-__device__ __forceinline__ long long wave_sum_i64(long long v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
-}
+__device__ __forceinline__ long long shfl_xor_i64(long long v, int mask) { return __shfl_xor(v, mask); }
 
-constexpr int kConvThreads = 256;
-
-// grid.x = nb * nb input blocks; block = 256 threads; bs in {16, 32, 64} (bs % 4 == 0).
-__global__ __launch_bounds__(kConvThreads) void conv_pool_kernel(const float* __restrict__ A, int L,
-                                                                  int bs, int p,
-                                                                  unsigned long long* __restrict__ pool) {
+// slots: 0 (0,0)  1 (-1,0)  2 (+1,0)  3 (0,-1)  4 (0,+1)  5 (-1,-1)  6 (+1,+1)  7 unused
+// grid.x = nb * nb input blocks; block = 64 * min(4, (bs/16)^2) threads; wave w walks the 16 x 16
+// sub-tiles w, w + nwaves, ... of the block, one float4 per lane per sub-tile.
+__global__ __launch_bounds__(256) void conv_pool_kernel(const float* __restrict__ A, int L, int bs, int p,
+                                                        unsigned long long* __restrict__ pool) {
     const int nb = L / bs;
     const int I = blockIdx.x / nb, J = blockIdx.x % nb;
-    const int tid = threadIdx.x;
-    const int vec_per_row = bs >> 2;             // float4 per block row
-    const int n_vec = bs * vec_per_row;          // float4 in the block
-
-    long long acc[7] = {0, 0, 0, 0, 0, 0, 0};   // (0,0) (-1,-1) (+1,+1) (-1,0) (0,-1) (+1,0) (0,+1)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int nsd = bs >> 4, nsub = nsd * nsd;
+    const int lr = lane >> 2, lc = (lane & 3) << 2;
     const float* base = A + (size_t)I * bs * L + (size_t)J * bs;
-    for (int idx = tid; idx < n_vec; idx += kConvThreads) {
-        const int u = idx / vec_per_row;
-        const int v0 = (idx % vec_per_row) << 2;
-        const float4 a4 = *reinterpret_cast<const float4*>(base + (size_t)u * L + v0);
-        const float av[4] = {a4.x, a4.y, a4.z, a4.w};
-        // row intervals
-        const int rm_lo = u + 1, rm_hi = p;                                   // di = -1
-        const int r0_lo = (u - bs + 1) > -p ? (u - bs + 1) : -p, r0_hi = u < p ? u : p;  // di = 0
-        const int rp_lo = -p, rp_hi = u - bs;                                 // di = +1
+
+    constexpr int kMaxSub = 4;   // sub-tiles per wave: (64/16)^2 / 4
+    float4 a4[kMaxSub];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int v = v0 + e;
-            const long long aq = __double2ll_rn((double)av[e] * 1099511627776.0);
-            const int cm_lo = v + 1, cm_hi = p;
-            const int c0_lo = (v - bs + 1) > -p ? (v - bs + 1) : -p, c0_hi = v < p ? v : p;
-            const int cp_lo = -p, cp_hi = v - bs;
-            acc[0] += (long long)isect(r0_lo, r0_hi, c0_lo, c0_hi) * aq;
-            acc[1] += (long long)isect(rm_lo, rm_hi, cm_lo, cm_hi) * aq;
-            acc[2] += (long long)isect(rp_lo, rp_hi, cp_lo, cp_hi) * aq;
-            acc[3] += (long long)isect(rm_lo, rm_hi, c0_lo, c0_hi) * aq;
-            acc[4] += (long long)isect(r0_lo, r0_hi, cm_lo, cm_hi) * aq;
-            acc[5] += (long long)isect(rp_lo, rp_hi, c0_lo, c0_hi) * aq;
-            acc[6] += (long long)isect(r0_lo, r0_hi, cp_lo, cp_hi) * aq;
+    for (int k = 0; k < kMaxSub; ++k) {
+        const int st = wave + k * nwaves;
+        if (st < nsub) {
+            const int u = (st / nsd) * 16 + lr, v0 = (st % nsd) * 16 + lc;
+            a4[k] = *reinterpret_cast<const float4*>(base + (size_t)u * L + v0);
         }
     }
 
-    __shared__ long long part[kConvThreads / 64][7];
-    const int wave = tid >> 6, lane = tid & 63;
+    long long tot[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    long long s_all = 0;
 #pragma unroll
-    for (int t = 0; t < 7; ++t) {
-        const long long s = wave_sum_i64(acc[t]);
-        if (lane == 0) part[wave][t] = s;
+    for (int k = 0; k < kMaxSub; ++k) {
+        const int st = wave + k * nwaves;
+        if (st >= nsub) break;
+        const int su = (st / nsd) * 16, sv = (st % nsd) * 16;
+        const int u = su + lr, v0 = sv + lc;
+        // wave-uniform: which neighbours can this sub-tile reach at all
+        const bool top = su < p, bottom = su + 15 > bs - 1 - p;
+        const bool left = sv < p, right = sv + 15 > bs - 1 - p;
+        const int rm_lo = u + 1, rm_hi = p;
+        const int r0_lo = (u - bs + 1) > -p ? (u - bs + 1) : -p, r0_hi = u < p ? u : p;
+        const int rp_lo = -p, rp_hi = u - bs;
+        const float av[4] = {a4[k].x, a4[k].y, a4[k].z, a4[k].w};
+        int s_hi = 0, s_lo = 0;
+        int n_hi[7] = {0, 0, 0, 0, 0, 0, 0}, n_lo[7] = {0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int v = v0 + e;
+            const float x = av[e] * 1048576.0f;
+            const float xf = floorf(x);
+            const int hi = (int)xf;
+            const int lo = (int)rintf((x - xf) * 1048576.0f);
+            s_hi += hi;
+            s_lo += lo;
+            const int cm_lo = v + 1, cm_hi = p;
+            const int c0_lo = (v - bs + 1) > -p ? (v - bs + 1) : -p, c0_hi = v < p ? v : p;
+            const int cp_lo = -p, cp_hi = v - bs;
+            if (top) {
+                const int w = isect(rm_lo, rm_hi, c0_lo, c0_hi);
+                n_hi[1] += w * hi;
+                n_lo[1] += w * lo;
+            }
+            if (bottom) {
+                const int w = isect(rp_lo, rp_hi, c0_lo, c0_hi);
+                n_hi[2] += w * hi;
+                n_lo[2] += w * lo;
+            }
+            if (left) {
+                const int w = isect(r0_lo, r0_hi, cm_lo, cm_hi);
+                n_hi[3] += w * hi;
+                n_lo[3] += w * lo;
+            }
+            if (right) {
+                const int w = isect(r0_lo, r0_hi, cp_lo, cp_hi);
+                n_hi[4] += w * hi;
+                n_lo[4] += w * lo;
+            }
+            if (top && left) {
+                const int w = isect(rm_lo, rm_hi, cm_lo, cm_hi);
+                n_hi[5] += w * hi;
+                n_lo[5] += w * lo;
+            }
+            if (bottom && right) {
+                const int w = isect(rp_lo, rp_hi, cp_lo, cp_hi);
+                n_hi[6] += w * hi;
+                n_lo[6] += w * lo;
+            }
+        }
+        // 4 elements * weight (< 128) * 2^21 fits 32 bits; widen once per sub-tile
+        s_all += ((long long)s_hi << 20) + s_lo;
+#pragma unroll
+        for (int t = 1; t < 7; ++t) tot[t] += ((long long)n_hi[t] << 20) + n_lo[t];
     }
-    __syncthreads();
-    if (tid < 7) {
-        long long s = 0;
+    long long others = 0;
 #pragma unroll
-        for (int w = 0; w < kConvThreads / 64; ++w) s += part[w][tid];
-        const int di_tab[7] = {0, -1, 1, -1, 0, 1, 0};
-        const int dj_tab[7] = {0, -1, 1, 0, -1, 0, 1};
-        const int ti = I + di_tab[tid], tj = J + dj_tab[tid];
-        if (s != 0 && ti >= 0 && ti < nb && tj >= 0 && tj < nb)
+    for (int t = 1; t < 7; ++t) others += tot[t];
+    tot[0] = (long long)(2 * p + 1) * s_all - others;
+
+    // reduce-scatter butterfly over the wave: 8 slots -> 4 -> 2 -> 1, then 3 plain steps
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const bool up = lane & 32;
+        const long long send = up ? tot[k] : tot[k + 4];
+        const long long keep = up ? tot[k + 4] : tot[k];
+        tot[k] = keep + shfl_xor_i64(send, 32);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const bool up = lane & 16;
+        const long long send = up ? tot[k] : tot[k + 2];
+        const long long keep = up ? tot[k + 2] : tot[k];
+        tot[k] = keep + shfl_xor_i64(send, 16);
+    }
+    {
+        const bool up = lane & 8;
+        const long long send = up ? tot[0] : tot[1];
+        const long long keep = up ? tot[1] : tot[0];
+        tot[0] = keep + shfl_xor_i64(send, 8);
+    }
+    long long s = tot[0];
+    s += shfl_xor_i64(s, 4);
+    s += shfl_xor_i64(s, 2);
+    s += shfl_xor_i64(s, 1);
+    if ((lane & 7) == 0) {
+        const int slot = ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
+        const int di_tab[8] = {0, -1, 1, 0, 0, -1, 1, 0};
+        const int dj_tab[8] = {0, 0, 0, -1, 1, -1, 1, 0};
+        const int ti = I + di_tab[slot], tj = J + dj_tab[slot];
+        if (slot < 7 && s != 0 && ti >= 0 && ti < nb && tj >= 0 && tj < nb)
             atomicAdd(&pool[(size_t)ti * nb + tj], (unsigned long long)s);
     }
 }
@@ -111,7 +182,10 @@ __global__ void zero_u64_kernel(unsigned long long* __restrict__ p, size_t n) {
 // threshold + fill + compaction (one workgroup)
 // ------------------------------------------------------------------------------------------------
 constexpr int kFinishThreads = 1024;
-constexpr unsigned kDown = 1u, kRight = 2u, kDiag = 4u;
+constexpr int kFinishWaves = kFinishThreads / 64;
+constexpr int SPION_MAX_NB_INTERNAL = 1024;   // same bound as SPION_MAX_NB of the public header
+constexpr unsigned kDown = 1u, kRight = 2u, kDiag = 4u, kAbove = 8u;
+constexpr unsigned kExpanded = 1u, kReached = 2u;
 
 struct Thresh {
     int is_int;
@@ -123,53 +197,83 @@ __device__ __forceinline__ bool above(long long x, const Thresh& t) {
     return t.is_int ? (x > t.ti) : ((double)x > t.td);
 }
 
-// Exclusive prefix sum over v[0..n) held one value per thread (n <= blockDim.x == 1024).
-// Returns the exclusive prefix of this thread's value; *total gets the sum.  All threads call.
-__device__ int block_exclusive_scan(int v, int* total, int* scratch /* [17] LDS */) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int incl = v;
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
+        const int o = __shfl_up(v, off);
+        if (lane >= off) v += o;
     }
+    return v;
+}
+
+// Exclusive prefix sum over one value per thread.  Returns the exclusive prefix of this thread's
+// value; *total gets the sum.  All threads call.  scratch: kFinishWaves + 1 ints of LDS.
+__device__ int block_exclusive_scan(int v, int* total, int* scratch) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int incl = wave_inclusive_scan(v, lane);
     if (lane == 63) scratch[wave] = incl;
     __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int w = 0; w < kFinishThreads / 64; ++w) {
-            const int c = scratch[w];
-            scratch[w] = run;
-            run += c;
-        }
-        scratch[16] = run;
+    if (wave == 0) {
+        const int c = lane < kFinishWaves ? scratch[lane] : 0;
+        const int inc = wave_inclusive_scan(c, lane);
+        if (lane < kFinishWaves) scratch[lane] = inc - c;
+        if (lane == kFinishWaves - 1) scratch[kFinishWaves] = inc;
     }
     __syncthreads();
     const int res = incl - v + scratch[wave];
-    *total = scratch[16];
+    *total = scratch[kFinishWaves];
     __syncthreads();
     return res;
 }
 
-// mode: 0 = threshold given in td (absolute), 1 = quantile rank k_rank, 2 = mean + kval * std.
-// mask / expd / pos are scratch arrays of nb*nb entries (global workspace).
+// Number of kept cells in a run of nb cells starting at f with the given element stride, counted by
+// one wave; with WRITE, also emits the compacted positions.
+template <bool WRITE>
+__device__ __forceinline__ int wave_compact(const uint8_t* f, int stride, int nb, int lane, int start,
+                                            int* idx_out, int* pos_rw, long long pos_base,
+                                            int pos_stride, int* bsr_pos_out) {
+    int offset = start;
+    for (int seg = 0; seg < nb; seg += 64) {
+        const int c = seg + lane;
+        const bool keep = c < nb && f[(long long)c * stride] != 0;
+        const unsigned long long b = __ballot(keep);
+        if (WRITE && keep) {
+            const int k = offset + __popcll(b & ((1ull << lane) - 1ull));
+            idx_out[k] = c;
+            if (bsr_pos_out)
+                bsr_pos_out[k] = pos_rw[pos_base + (long long)c * pos_stride];
+            else
+                pos_rw[pos_base + (long long)c * pos_stride] = k;
+        }
+        offset += __popcll(b);
+    }
+    return offset - start;
+}
+
+// mode: 0 = threshold given in t_abs, 1 = quantile rank k_rank, 2 = mean + kval * std.
+// mask_g / expd_g / pos: scratch arrays of nb*nb entries in global memory; when use_lds is set the
+// two byte arrays live in dynamic LDS instead (2 * nb * nb bytes).
 __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     const long long* __restrict__ pool, int nb, int mode, long long k_rank, double kval, double t_abs,
-    int no_fill, uint8_t* __restrict__ mask, uint8_t* __restrict__ expd, int* __restrict__ pos,
+    int no_fill, int use_lds, uint8_t* mask_g, uint8_t* expd_g, int* __restrict__ pos,
     uint8_t* __restrict__ fl, int* __restrict__ row_ptr, int* __restrict__ col_idx,
     int* __restrict__ col_ptr, int* __restrict__ row_idx, int* __restrict__ bsr_pos,
     int* __restrict__ nnzb_out) {
-    const int tid = threadIdx.x;
+    extern __shared__ uint8_t dyn_lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long long n = (long long)nb * nb;
+    uint8_t* mask = use_lds ? dyn_lds : mask_g;
+    uint8_t* expd = use_lds ? dyn_lds + n : expd_g;
     __shared__ unsigned hist[256];
     __shared__ Thresh th;
     __shared__ unsigned long long sel_prefix;
     __shared__ long long sel_k;
-    __shared__ int scan_scratch[17];
+    __shared__ int scan_scratch[kFinishWaves + 1];
+    __shared__ int line_start[SPION_MAX_NB_INTERNAL];
 
     // ---- 1. threshold ------------------------------------------------------------------------
     if (mode == 1) {
-        // exact k-th smallest (0-based) by most-significant-byte-first radix selection
+        // exact k-th smallest (0-based): most-significant-byte-first radix selection
         if (tid == 0) {
             sel_prefix = 0ull;
             sel_k = k_rank;
@@ -179,22 +283,19 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
             if (tid < 256) hist[tid] = 0u;
             __syncthreads();
             const unsigned long long prefix = sel_prefix;
+            const long long k = sel_k;
             for (long long i = tid; i < n; i += kFinishThreads) {
                 const unsigned long long u = (unsigned long long)pool[i] ^ 0x8000000000000000ull;
                 const bool match = (pass == 7) || ((u >> (shift + 8)) == (prefix >> (shift + 8)));
                 if (match) atomicAdd(&hist[(unsigned)((u >> shift) & 0xFFull)], 1u);
             }
             __syncthreads();
-            if (tid == 0) {
-                long long k = sel_k;
-                int b = 0;
-                for (; b < 255; ++b) {
-                    const long long c = hist[b];
-                    if (k < c) break;
-                    k -= c;
-                }
-                sel_k = k;
-                sel_prefix = prefix | ((unsigned long long)b << shift);
+            // the bin b with excl(b) <= k < incl(b): found by a 256-wide scan
+            int c = tid < 256 ? (int)hist[tid] : 0, total = 0;
+            const int excl = block_exclusive_scan(c, &total, scan_scratch);
+            if (tid < 256 && c > 0 && k >= excl && k < (long long)excl + c) {
+                sel_k = k - excl;
+                sel_prefix = prefix | ((unsigned long long)tid << shift);
             }
             __syncthreads();
         }
@@ -232,87 +333,123 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     __syncthreads();
     const Thresh t = th;
 
-    if (no_fill) {
-        // SPION-C: keep every block above the threshold
-        for (long long i = tid; i < n; i += kFinishThreads) fl[i] = above(pool[i], t) ? 1 : 0;
-    } else {
-        // ---- 2. successor bits: which of (down, right, diag) equal their maximum ------------------
-        for (long long i = tid; i < n; i += kFinishThreads) {
-            const int r = (int)(i / nb), c = (int)(i % nb);
-            unsigned m = 0u;
-            if (r + 1 < nb && c + 1 < nb) {
-                const long long dn = pool[i + nb], rt = pool[i + 1], dg = pool[i + nb + 1];
-                long long mx = dn > rt ? dn : rt;
-                mx = mx > dg ? mx : dg;
-                m = (dn == mx ? kDown : 0u) | (rt == mx ? kRight : 0u) | (dg == mx ? kDiag : 0u);
-            }
-            mask[i] = (uint8_t)m;
-            expd[i] = (r == 0 || c == 0) ? 1 : 0;     // seeds: first row and first column
-            fl[i] = 0;
+    // ---- 2. per cell: successor bits (which of down / right / diag equal their maximum), the
+    //         "above threshold" bit, and the seed flag (first row and first column) ------------------
+    for (long long i = tid; i < n; i += kFinishThreads) {
+        const int r = (int)(i / nb), c = (int)(i % nb);
+        const long long x = pool[i];
+        unsigned m = above(x, t) ? kAbove : 0u;
+        if (r + 1 < nb && c + 1 < nb) {
+            const long long dn = pool[i + nb], rt = pool[i + 1], dg = pool[i + nb + 1];
+            long long mx = dn > rt ? dn : rt;
+            mx = mx > dg ? mx : dg;
+            m |= (dn == mx ? kDown : 0u) | (rt == mx ? kRight : 0u) | (dg == mx ? kDiag : 0u);
         }
-        __syncthreads();
-        // ---- 3. fill: every move raises r + c, so anti-diagonal s depends only on s-1 and s-2 ----
-        // A cell is reached iff an expanded predecessor lists it as a successor; reached cells are
-        // expanded in turn (marked or not) and marked iff above the threshold.
-        for (int s = 1; s <= 2 * nb - 2; ++s) {
-            const int r = tid, c = s - tid;
-            if (r < nb && c >= 0 && c < nb) {
-                const long long i = (long long)r * nb + c;
-                bool reached = false;
-                if (r >= 1) reached |= expd[i - nb] && (mask[i - nb] & kDown);
-                if (c >= 1) reached |= expd[i - 1] && (mask[i - 1] & kRight);
-                if (r >= 1 && c >= 1) reached |= expd[i - nb - 1] && (mask[i - nb - 1] & kDiag);
-                if (reached) {
-                    expd[i] = 1;
-                    if (above(pool[i], t)) fl[i] = 1;
-                }
-            }
-            __syncthreads();
-        }
+        mask[i] = (uint8_t)m;
+        expd[i] = no_fill ? (uint8_t)kReached : ((r == 0 || c == 0) ? (uint8_t)kExpanded : (uint8_t)0);
     }
-    __syncthreads();
-    // ---- 4. forced diagonal ------------------------------------------------------------------------
-    if (tid < nb) fl[(long long)tid * nb + tid] = 1;
     __syncthreads();
 
-    // ---- 5. compaction: BSR (rows), then BSC (columns) ---------------------------------------------
-    int cnt = 0;
-    if (tid < nb)
-        for (int c = 0; c < nb; ++c) cnt += fl[(long long)tid * nb + c];
-    int total = 0;
-    int start = block_exclusive_scan(cnt, &total, scan_scratch);
-    if (tid < nb) {
-        row_ptr[tid] = start;
-        int k = start;
-        for (int c = 0; c < nb; ++c) {
-            if (fl[(long long)tid * nb + c]) {
-                col_idx[k] = c;
-                pos[(long long)tid * nb + c] = k;
-                ++k;
+    // ---- 3. fill: every move raises r + c, so anti-diagonal s depends only on s-1 and s-2.  A cell is
+    //         reached iff an expanded predecessor lists it as a successor; reached cells are expanded
+    //         in turn whether or not they exceed the threshold. -------------------------------------
+    if (!no_fill) {
+        if (nb <= 64) {
+            // one wave, lane = row; the outgoing successor bits of the previous two anti-diagonals
+            // travel in registers, the neighbour row's bits arrive by a one-lane shift
+            if (wave == 0) {
+                const int r = lane;
+                unsigned out1 = 0u, out2 = 0u;
+                unsigned m_next = (r == 0) ? mask[0] : 0u;
+                for (int s = 0; s <= 2 * nb - 2; ++s) {
+                    const int c = s - r;
+                    const bool valid = r < nb && c >= 0 && c < nb;
+                    const unsigned m = m_next;
+                    const int c1 = c + 1;   // prefetch the next anti-diagonal's bits
+                    m_next = (r < nb && c1 >= 0 && c1 < nb) ? mask[(long long)r * nb + c1] : 0u;
+                    const unsigned both = out1 | (out2 << 8);
+                    const unsigned up = __builtin_amdgcn_update_dpp(0u, both, 0x138 /* wave_shr:1 */,
+                                                                    0xf, 0xf, false);
+                    const bool reached =
+                        valid && ((out1 & kRight) || (up & kDown) || ((up >> 8) & kDiag));
+                    const bool expanded = valid && (reached || r == 0 || c == 0);
+                    if (reached) expd[(long long)r * nb + c] = (uint8_t)(kExpanded | kReached);
+                    out2 = out1;
+                    out1 = expanded ? (m & 7u) : 0u;
+                }
+            }
+        } else {
+            for (int s = 1; s <= 2 * nb - 2; ++s) {
+                const int r = tid, c = s - tid;
+                if (r < nb && c >= 0 && c < nb) {
+                    const long long i = (long long)r * nb + c;
+                    bool reached = false;
+                    if (r >= 1) reached |= (expd[i - nb] & kExpanded) && (mask[i - nb] & kDown);
+                    if (c >= 1) reached |= (expd[i - 1] & kExpanded) && (mask[i - 1] & kRight);
+                    if (r >= 1 && c >= 1)
+                        reached |= (expd[i - nb - 1] & kExpanded) && (mask[i - nb - 1] & kDiag);
+                    if (reached) expd[i] = (uint8_t)(kExpanded | kReached);
+                }
+                __syncthreads();
             }
         }
     }
-    if (tid == 0) {
-        row_ptr[nb] = total;
-        *nnzb_out = total;
+    __syncthreads();
+    // ---- 4. fl_out = reached and above the threshold, or on the diagonal; kept in expd for step 5 ---
+    for (long long i = tid; i < n; i += kFinishThreads) {
+        const int r = (int)(i / nb), c = (int)(i % nb);
+        const uint8_t f = (((expd[i] & kReached) && (mask[i] & kAbove)) || r == c) ? 1 : 0;
+        fl[i] = f;
+        mask[i] = f;
+    }
+    __syncthreads();
+
+    // ---- 5. compaction: BSR (rows), then BSC (columns); one wave per row / column ------------------
+    int total = 0;
+    {
+        int cnt = 0;
+        for (int r = wave; r < nb; r += kFinishWaves) {
+            const int k = wave_compact<false>(mask + (long long)r * nb, 1, nb, lane, 0, nullptr, nullptr, 0,
+                                              0, nullptr);
+            if (lane == 0) line_start[r] = k;
+        }
+        __syncthreads();
+        for (int base = 0; base < nb; base += kFinishThreads) {   // nb <= 1024: one round
+            cnt = (base + tid < nb) ? line_start[base + tid] : 0;
+            const int start = block_exclusive_scan(cnt, &total, scan_scratch);
+            if (base + tid < nb) {
+                line_start[base + tid] = start;
+                row_ptr[base + tid] = start;
+            }
+        }
+        __syncthreads();
+        for (int r = wave; r < nb; r += kFinishWaves)
+            wave_compact<true>(mask + (long long)r * nb, 1, nb, lane, line_start[r], col_idx, pos,
+                               (long long)r * nb, 1, nullptr);
+        if (tid == 0) {
+            row_ptr[nb] = total;
+            *nnzb_out = total;
+        }
     }
     if (col_ptr != nullptr) {
         __syncthreads();
-        cnt = 0;
-        if (tid < nb)
-            for (int r = 0; r < nb; ++r) cnt += fl[(long long)r * nb + tid];
-        start = block_exclusive_scan(cnt, &total, scan_scratch);
-        if (tid < nb) {
-            col_ptr[tid] = start;
-            int k = start;
-            for (int r = 0; r < nb; ++r) {
-                if (fl[(long long)r * nb + tid]) {
-                    row_idx[k] = r;
-                    bsr_pos[k] = pos[(long long)r * nb + tid];
-                    ++k;
-                }
+        for (int c = wave; c < nb; c += kFinishWaves) {
+            const int k = wave_compact<false>(mask + c, nb, nb, lane, 0, nullptr, nullptr, 0, 0, nullptr);
+            if (lane == 0) line_start[c] = k;
+        }
+        __syncthreads();
+        for (int base = 0; base < nb; base += kFinishThreads) {
+            const int cnt = (base + tid < nb) ? line_start[base + tid] : 0;
+            const int start = block_exclusive_scan(cnt, &total, scan_scratch);
+            if (base + tid < nb) {
+                line_start[base + tid] = start;
+                col_ptr[base + tid] = start;
             }
         }
+        __syncthreads();
+        for (int c = wave; c < nb; c += kFinishWaves)
+            wave_compact<true>(mask + c, nb, nb, lane, line_start[c], row_idx, pos, (long long)c, nb,
+                               bsr_pos);
         if (tid == 0) col_ptr[nb] = total;
     }
 }
@@ -325,7 +462,9 @@ hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* poo
     const size_t n = (size_t)nb * nb;
     zero_u64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(
         reinterpret_cast<unsigned long long*>(pool), n);
-    conv_pool_kernel<<<dim3((unsigned)n), dim3(kConvThreads), 0, st>>>(
+    const int nsub = (bs / 16) * (bs / 16);
+    const int threads = 64 * (nsub < 4 ? nsub : 4);
+    conv_pool_kernel<<<dim3((unsigned)n), dim3(threads), 0, st>>>(
         A, L, bs, p, reinterpret_cast<unsigned long long*>(pool));
     return hipGetLastError();
 }
@@ -334,9 +473,11 @@ hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long l
                                  double t_abs, int no_fill, uint8_t* mask, uint8_t* expd, int* pos,
                                  uint8_t* fl, int* row_ptr, int* col_idx, int* col_ptr, int* row_idx,
                                  int* bsr_pos, int* nnzb, hipStream_t st) {
-    pattern_finish_kernel<<<dim3(1), dim3(kFinishThreads), 0, st>>>(
-        pool, nb, mode, k_rank, kval, t_abs, no_fill, mask, expd, pos, fl, row_ptr, col_idx, col_ptr,
-        row_idx, bsr_pos, nnzb);
+    const size_t n = (size_t)nb * nb;
+    const int use_lds = 2 * n <= 48 * 1024 ? 1 : 0;   // keeps static + dynamic LDS under 64 KB
+    pattern_finish_kernel<<<dim3(1), dim3(kFinishThreads), use_lds ? 2 * n : 0, st>>>(
+        pool, nb, mode, k_rank, kval, t_abs, no_fill, use_lds, mask, expd, pos, fl, row_ptr, col_idx,
+        col_ptr, row_idx, bsr_pos, nnzb);
     return hipGetLastError();
 }
 

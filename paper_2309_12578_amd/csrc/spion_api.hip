@@ -93,7 +93,7 @@ int spion_pattern(const float* A_s, const spion_pattern_params* p, uint8_t* fl_o
     if (any_bsc && !(col_ptr && row_idx && bsr_pos)) return SPION_ERR_NULL;
     if (!shape_ok(p->L, p->block)) return SPION_ERR_SHAPE;
     const int32_t bs = p->block, nb = p->L / bs;
-    if (p->filter < 1 || (p->filter % 2) == 0 || (p->filter - 1) / 2 > bs) return SPION_ERR_PARAM;
+    if (p->filter < 1 || (p->filter % 2) == 0 || (p->filter - 1) / 2 >= bs) return SPION_ERR_PARAM;
     if (p->reserved != 0 || (p->flags & ~SPION_PATTERN_NO_FILL)) return SPION_ERR_PARAM;
     const int64_t n = (int64_t)nb * nb;
     int mode = 0;
@@ -145,7 +145,7 @@ int spion_pattern(const float* A_s, const spion_pattern_params* p, uint8_t* fl_o
 size_t spion_attn_workspace_bytes(const spion_attn_params* p, int32_t nnzb, int32_t is_bwd) {
     if (!p || attn_params_ok(p, nnzb) != SPION_OK) return (size_t)-1;
     if (!is_bwd) return 0;
-    return align_up((size_t)p->B * p->H * p->L * sizeof(float));   // delta = rowsum(dO .* O)
+    return spion::attn_bwd_workspace_bytes(p->B * p->H, p->L, p->block, p->L / p->block, nnzb);
 }
 
 int spion_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
@@ -179,8 +179,7 @@ int spion_attn_bwd(const void* Q, const void* K, const void* V, const void* O, c
         return SPION_ERR_WORKSPACE;
     const spion::AttnShape s = make_shape(p);
     if (spion::launch_attn_bwd(s, Q, K, V, O, dO, LSE, dQ, dK, dV, row_ptr, col_idx, col_ptr, row_idx,
-                               static_cast<float*>(workspace),
-                               static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+                               nnzb, workspace, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return SPION_ERR_HIP;
     return SPION_OK;
 }

@@ -28,7 +28,16 @@ hipError_t launch_attn_fwd(const AttnShape& s, const void* Q, const void* K, con
 hipError_t launch_attn_bwd(const AttnShape& s, const void* Q, const void* K, const void* V,
                            const void* O, const void* dO, const float* LSE, void* dQ, void* dK,
                            void* dV, const int* row_ptr, const int* col_idx, const int* col_ptr,
-                           const int* row_idx, float* delta, hipStream_t st);
+                           const int* row_idx, int nnzb, void* workspace, hipStream_t st);
+
+// Carving of the backward workspace: delta = rowsum(dO .* O) per query, the key-side work list, and
+// fp32 partial dK / dV tiles for block columns that are cut into several chunks.
+struct BwdWorkspace {
+    int w_max, n_slots;
+    size_t delta_off, sched_off, colinfo_off, partial_off, total;
+    BwdWorkspace(int BH, int L, int bs, int nb, int nnzb);
+};
+size_t attn_bwd_workspace_bytes(int BH, int L, int bs, int nb, int nnzb);
 
 }  // namespace spion
 #endif
