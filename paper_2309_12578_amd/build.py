@@ -20,6 +20,7 @@ SOURCES = [
     ("spion_api.hip", ["-ffp-contract=off"]),
     ("pattern_kernels.hip", ["-ffp-contract=off"]),
     ("attn_kernels.hip", []),
+    ("attn_bf16_kernels.hip", []),
 ]
 
 

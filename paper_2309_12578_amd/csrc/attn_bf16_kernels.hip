@@ -1,0 +1,467 @@
+// bf16 block-sparse attention kernels tuned for gfx950, block size 32 or 64.
+//
+// Same mathematics and wave tiling as the generic kernels (16 owned rows per wave on the N index of
+// every MFMA tile), plus:
+//   - tiles stay row-major in LDS; operands that must be read along the row index (V for O = P V,
+//     K for dQ, Q and dO for dK / dV) come out of the same tile through the LDS transpose read
+//     (ds_read_b64_tr_b16: 16 lanes fetch a 4 x 16 patch and each receives one column of it);
+//   - LDS tiles are double buffered and the next tile travels HBM -> registers while the current one
+//     is multiplied, so a kept block costs one barrier and no exposed memory round trip;
+//   - workgroup ids are remapped so that each of the 8 XCDs (one L2 each) works on whole heads.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "attn_common.h"
+#include "spion_internal.h"
+
+namespace spion {
+
+constexpr int kLd = kD + 8;   // LDS row stride in bf16 elements (144 B: 16-byte aligned, bank-skewed)
+
+__device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
+    typedef bf16x4 __attribute__((address_space(3))) * lds_ptr;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)p);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Workgroups are dealt round-robin to the 8 XCDs in id order.  Give XCD x the x-th contiguous
+// eighth of the (head-major) work so that the K / V (or Q / dO) rows of a head stay in one L2.
+__device__ __forceinline__ int xcd_remap(int id, int total) {
+    if (total & 7) return id;
+    return (id & 7) * (total >> 3) + (id >> 3);
+}
+
+// One bs x 64 bf16 tile = bs * 8 fragments of 16 B; a workgroup of 4 * bs threads moves 2 each.
+template <int BS>
+struct TileRegs {
+    bf16x8 f[2];
+    __device__ __forceinline__ void load(const bf16_t* __restrict__ src, int tid) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+            f[it] = *reinterpret_cast<const bf16x8*>(src + (size_t)(it * BS * 4 + tid) * 8);
+    }
+    __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int idx = it * BS * 4 + tid;
+            *reinterpret_cast<bf16x8*>(lds + (idx >> 3) * kLd + (idx & 7) * 8) = f[it];
+        }
+    }
+};
+
+// acc[dt][i] (d = 16 dt + 4 g + i, owned row r) += sum over the tile's rows of
+// tile[row][16 dt + ...] * x[row][r], with x given as accumulator-layout tiles of 16 rows.
+template <int BS>
+__device__ __forceinline__ void mma_over_rows_tr(f32x4 (&acc)[4], const bf16_t* tile,
+                                                 const bf16x4 (&x)[BS / 16], int r, int g) {
+    const bf16_t* base = tile + (4 * g + (r >> 2)) * kLd + 4 * (r & 3);
+#pragma unroll
+    for (int pc = 0; pc < BS / 32; ++pc) {
+        const bf16x8 xf = join(x[2 * pc], x[2 * pc + 1]);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            const bf16x4 lo = lds_read_tr(base + (pc * 32) * kLd + dt * 16);
+            const bf16x4 hi = lds_read_tr(base + (pc * 32 + 16) * kLd + dt * 16);
+            acc[dt] = mma_d(acc[dt], join(lo, hi), xf);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------------
+template <int BS>
+__global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    bf16_t* __restrict__ O, float* __restrict__ LSE, const int* __restrict__ row_ptr,
+    const int* __restrict__ col_idx, int L, int nb, int total, float scale_log2, int paper_denom) {
+    constexpr int NKT = BS / 16;
+    __shared__ __attribute__((aligned(16))) bf16_t k_s[2][BS * kLd];
+    __shared__ __attribute__((aligned(16))) bf16_t v_s[2][BS * kLd];
+
+    const int vid = xcd_remap(blockIdx.x, total);
+    const int I = vid % nb, bh = vid / nb;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const size_t head = (size_t)bh * L * kD;
+    const int qrow = I * BS + wave * 16 + r;
+    const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
+
+    TileRegs<BS> kreg, vreg;
+    if (n > 0) {
+        const size_t t0 = head + (size_t)col_idx[jb] * BS * kD;
+        kreg.load(K + t0, tid);
+        vreg.load(V + t0, tid);
+    }
+    bf16x8 qf[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+        qf[c] = *reinterpret_cast<const bf16x8*>(Q + head + (size_t)qrow * kD + c * 32 + g * 8);
+    if (n > 0) {
+        kreg.store(k_s[0], tid);
+        vreg.store(v_s[0], tid);
+    }
+    if (n > 1) {
+        const size_t t1 = head + (size_t)col_idx[jb + 1] * BS * kD;
+        kreg.load(K + t1, tid);
+        vreg.load(V + t1, tid);
+    }
+    __syncthreads();
+
+    float m = -INFINITY, lsum = 0.f;   // m in log2 units (score * scale * log2 e)
+    f32x4 oacc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int it = 0; it < n; ++it) {
+        const int buf = it & 1;
+        if (it + 1 < n) {   // tile it+1 has landed in registers during the previous multiply
+            kreg.store(k_s[buf ^ 1], tid);
+            vreg.store(v_s[buf ^ 1], tid);
+        }
+        if (it + 2 < n) {
+            const size_t t2 = head + (size_t)col_idx[jb + it + 2] * BS * kD;
+            kreg.load(K + t2, tid);
+            vreg.load(V + t2, tid);
+        }
+        const bf16_t* kt_s = k_s[buf];
+        // S^T tile kt: [key 16 kt + 4 g + i][query r]
+        f32x4 s[NKT];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+            s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kt_s + (kt * 16 + r) * kLd + c * 32 + g * 8);
+                s[kt] = mma_d(s[kt], kf, qf[c]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[kt][i]);
+        }
+        mx = group_max(mx);
+        const float m_new = fmaxf(m, mx * scale_log2);
+        const float alpha = fast_exp2(m - m_new);
+        lsum *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
+        bf16x4 pq[NKT];
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p = fast_exp2(fmaf(s[kt][i], scale_log2, -m_new));
+                s[kt][i] = p;
+                lsum += p;
+            }
+            pq[kt] = to_quad<bf16_t>(s[kt]);
+        }
+        m = m_new;
+        mma_over_rows_tr<BS>(oacc, v_s[buf], pq, r, g);   // O^T[d][query] += V^T P^T
+        __syncthreads();
+    }
+
+    lsum = group_sum(lsum);
+    if (paper_denom) {
+        // Algorithm 6: every masked entry of the row counts as a score of 0
+        const float masked = (float)(L - n * BS);
+        const float mp = fmaxf(m, 0.f);
+        const float a = exp2f(m - mp);
+        lsum = lsum * a + masked * exp2f(-mp);
+        m = mp;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) oacc[dt] *= a;
+    }
+    const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+    bf16_t* orow = O + head + (size_t)qrow * kD;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) store_quad<bf16_t>(orow + dt * 16 + 4 * g, oacc[dt] * inv);
+    if (g == 0) LSE[(size_t)bh * L + qrow] = lsum > 0.f ? (m + log2f(lsum)) * kLn2 : -INFINITY;
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, query side: delta = rowsum(dO .* O), dQ; also builds the key-side work list
+// ------------------------------------------------------------------------------------------------
+template <int BS>
+__global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, const float* __restrict__ LSE,
+    bf16_t* __restrict__ dQ, float* __restrict__ delta_out, const int* __restrict__ row_ptr,
+    const int* __restrict__ col_idx, const int* __restrict__ col_ptr, int w_max,
+    int4* __restrict__ sched, int2* __restrict__ colinfo, int L, int nb, int total, float scale,
+    float scale_log2) {
+    constexpr int NKT = BS / 16;
+    __shared__ __attribute__((aligned(16))) bf16_t k_s[2][BS * kLd];
+    __shared__ __attribute__((aligned(16))) bf16_t v_s[2][BS * kLd];
+
+    const int vid = xcd_remap(blockIdx.x, total);
+    const int I = vid % nb, bh = vid / nb;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const size_t head = (size_t)bh * L * kD;
+    const int qrow = I * BS + wave * 16 + r;
+    const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
+
+    TileRegs<BS> kreg, vreg;
+    if (n > 0) {
+        const size_t t0 = head + (size_t)col_idx[jb] * BS * kD;
+        kreg.load(K + t0, tid);
+        vreg.load(V + t0, tid);
+    }
+    if (vid == 0 && tid < 64) build_key_schedule(col_ptr, nb, w_max, sched, colinfo, tid);
+
+    bf16x8 qf[2], dof[2];
+    float delta = 0.f;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const size_t off = head + (size_t)qrow * kD + c * 32 + g * 8;
+        qf[c] = *reinterpret_cast<const bf16x8*>(Q + off);
+        dof[c] = *reinterpret_cast<const bf16x8*>(dO + off);
+        const bf16x8 of = *reinterpret_cast<const bf16x8*>(O + off);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) delta = fmaf((float)dof[c][e], (float)of[e], delta);
+    }
+    delta = group_sum(delta);
+    if (g == 0) delta_out[(size_t)bh * L + qrow] = delta;
+    const float lse2 = LSE[(size_t)bh * L + qrow] * kLog2e;
+
+    if (n > 0) {
+        kreg.store(k_s[0], tid);
+        vreg.store(v_s[0], tid);
+    }
+    if (n > 1) {
+        const size_t t1 = head + (size_t)col_idx[jb + 1] * BS * kD;
+        kreg.load(K + t1, tid);
+        vreg.load(V + t1, tid);
+    }
+    __syncthreads();
+
+    f32x4 dq[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) dq[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int it = 0; it < n; ++it) {
+        const int buf = it & 1;
+        if (it + 1 < n) {
+            kreg.store(k_s[buf ^ 1], tid);
+            vreg.store(v_s[buf ^ 1], tid);
+        }
+        if (it + 2 < n) {
+            const size_t t2 = head + (size_t)col_idx[jb + it + 2] * BS * kD;
+            kreg.load(K + t2, tid);
+            vreg.load(V + t2, tid);
+        }
+        bf16x4 dsq[NKT];
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, dp = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int off = (kt * 16 + r) * kLd + c * 32 + g * 8;
+                s = mma_d(s, *reinterpret_cast<const bf16x8*>(k_s[buf] + off), qf[c]);     // S^T = K Q^T
+                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(v_s[buf] + off), dof[c]);  // dP^T = V dO^T
+            }
+            f32x4 ds;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p = fast_exp2(fmaf(s[i], scale_log2, -lse2));
+                ds[i] = p * (dp[i] - delta);
+            }
+            dsq[kt] = to_quad<bf16_t>(ds);
+        }
+        mma_over_rows_tr<BS>(dq, k_s[buf], dsq, r, g);   // dQ^T[d][query] += K^T dS^T
+        __syncthreads();
+    }
+    bf16_t* drow = dQ + head + (size_t)qrow * kD;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) store_quad<bf16_t>(drow + dt * 16 + 4 * g, dq[dt] * scale);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, key side: one work item (a chunk of the kept rows of one block column) per workgroup
+// ------------------------------------------------------------------------------------------------
+template <int BS>
+__global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, const int* __restrict__ row_idx,
+    const int4* __restrict__ sched, int w_max, int total, int n_slots, float* __restrict__ partial, int L,
+    float scale, float scale_log2) {
+    constexpr int NQT = BS / 16;
+    __shared__ __attribute__((aligned(16))) bf16_t q_s[2][BS * kLd];
+    __shared__ __attribute__((aligned(16))) bf16_t do_s[2][BS * kLd];
+    __shared__ __attribute__((aligned(16))) float lse_s[2][BS];
+    __shared__ __attribute__((aligned(16))) float delta_s[2][BS];
+
+    const int vid = xcd_remap(blockIdx.x, total);
+    const int w = vid % w_max, bh = vid / w_max;
+    const int4 item = sched[w];
+    const int J = item.x, kb = item.y, n = item.z - item.y, slot = item.w;
+    if (J < 0) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const size_t head = (size_t)bh * L * kD;
+    const size_t vec = (size_t)bh * L;
+    const int krow = J * BS + wave * 16 + r;
+
+    TileRegs<BS> qreg, doreg;
+    float lse_r = 0.f, delta_r = 0.f;
+    if (n > 0) {
+        const int I0 = row_idx[kb];
+        qreg.load(Q + head + (size_t)I0 * BS * kD, tid);
+        doreg.load(dO + head + (size_t)I0 * BS * kD, tid);
+        if (tid < BS) {
+            lse_r = LSE[vec + I0 * BS + tid];
+            delta_r = delta[vec + I0 * BS + tid];
+        }
+    }
+    bf16x8 kf[2], vf[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const size_t off = head + (size_t)krow * kD + c * 32 + g * 8;
+        kf[c] = *reinterpret_cast<const bf16x8*>(K + off);
+        vf[c] = *reinterpret_cast<const bf16x8*>(V + off);
+    }
+    if (n > 0) {
+        qreg.store(q_s[0], tid);
+        doreg.store(do_s[0], tid);
+        if (tid < BS) {
+            lse_s[0][tid] = lse_r * kLog2e;
+            delta_s[0][tid] = delta_r;
+        }
+    }
+    if (n > 1) {
+        const int I1 = row_idx[kb + 1];
+        qreg.load(Q + head + (size_t)I1 * BS * kD, tid);
+        doreg.load(dO + head + (size_t)I1 * BS * kD, tid);
+        if (tid < BS) {
+            lse_r = LSE[vec + I1 * BS + tid];
+            delta_r = delta[vec + I1 * BS + tid];
+        }
+    }
+    __syncthreads();
+
+    f32x4 dk[4], dv[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        dk[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        dv[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int it = 0; it < n; ++it) {
+        const int buf = it & 1;
+        if (it + 1 < n) {
+            qreg.store(q_s[buf ^ 1], tid);
+            doreg.store(do_s[buf ^ 1], tid);
+            if (tid < BS) {
+                lse_s[buf ^ 1][tid] = lse_r * kLog2e;
+                delta_s[buf ^ 1][tid] = delta_r;
+            }
+        }
+        if (it + 2 < n) {
+            const int I2 = row_idx[kb + it + 2];
+            qreg.load(Q + head + (size_t)I2 * BS * kD, tid);
+            doreg.load(dO + head + (size_t)I2 * BS * kD, tid);
+            if (tid < BS) {
+                lse_r = LSE[vec + I2 * BS + tid];
+                delta_r = delta[vec + I2 * BS + tid];
+            }
+        }
+        bf16x4 pq[NQT], dsq[NQT];
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, dp = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int off = (qt * 16 + r) * kLd + c * 32 + g * 8;
+                s = mma_d(s, *reinterpret_cast<const bf16x8*>(q_s[buf] + off), kf[c]);     // S = Q K^T
+                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(do_s[buf] + off), vf[c]);  // dP = dO V^T
+            }
+            const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&lse_s[buf][qt * 16 + 4 * g]);
+            const f32x4 del4 = *reinterpret_cast<const f32x4*>(&delta_s[buf][qt * 16 + 4 * g]);
+            f32x4 p, ds;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                p[i] = fast_exp2(fmaf(s[i], scale_log2, -lse4[i]));
+                ds[i] = p[i] * (dp[i] - del4[i]);
+            }
+            pq[qt] = to_quad<bf16_t>(p);
+            dsq[qt] = to_quad<bf16_t>(ds);
+        }
+        mma_over_rows_tr<BS>(dv, do_s[buf], pq, r, g);   // dV^T[d][key] += dO^T P
+        mma_over_rows_tr<BS>(dk, q_s[buf], dsq, r, g);   // dK^T[d][key] += Q^T dS
+        __syncthreads();
+    }
+    if (slot < 0) {
+        bf16_t* dkrow = dK + head + (size_t)krow * kD;
+        bf16_t* dvrow = dV + head + (size_t)krow * kD;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            store_quad<bf16_t>(dkrow + dt * 16 + 4 * g, dk[dt] * scale);
+            store_quad<bf16_t>(dvrow + dt * 16 + 4 * g, dv[dt]);
+        }
+    } else {
+        float* pk = partial + ((size_t)bh * n_slots + slot) * (2 * BS * kD) + (size_t)(wave * 16 + r) * kD;
+        float* pv = pk + BS * kD;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            *reinterpret_cast<f32x4*>(pk + dt * 16 + 4 * g) = dk[dt];
+            *reinterpret_cast<f32x4*>(pv + dt * 16 + 4 * g) = dv[dt];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// launchers (called by the dispatch in attn_kernels.hip)
+// ------------------------------------------------------------------------------------------------
+template <int BS>
+hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                    const int* row_ptr, const int* col_idx, hipStream_t st) {
+    const int total = s.nb * s.BH;
+    attn_fwd_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+        static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
+        static_cast<bf16_t*>(O), LSE, row_ptr, col_idx, s.L, s.nb, total, s.scale * kLog2e, s.paper_denom);
+    return hipGetLastError();
+}
+
+template <int BS>
+hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
+                       const void* dO, const float* LSE, void* dQ, float* delta, const int* row_ptr,
+                       const int* col_idx, const int* col_ptr, int w_max, int4* sched, int2* colinfo,
+                       hipStream_t st) {
+    const int total = s.nb * s.BH;
+    attn_bwd_dq_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+        static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
+        static_cast<const bf16_t*>(O), static_cast<const bf16_t*>(dO), LSE, static_cast<bf16_t*>(dQ), delta,
+        row_ptr, col_idx, col_ptr, w_max, sched, colinfo, s.L, s.nb, total, s.scale, s.scale * kLog2e);
+    return hipGetLastError();
+}
+
+template <int BS>
+hipError_t bwd_dkv_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* dO,
+                        const float* LSE, const float* delta, void* dK, void* dV, const int* row_idx,
+                        const int4* sched, int w_max, int n_slots, float* partial, hipStream_t st) {
+    const int total = w_max * s.BH;
+    attn_bwd_dkv_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+        static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
+        static_cast<const bf16_t*>(dO), LSE, delta, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV),
+        row_idx, sched, w_max, total, n_slots, partial, s.L, s.scale, s.scale * kLog2e);
+    return hipGetLastError();
+}
+
+template hipError_t fwd_bf16<32>(const AttnShape&, const void*, const void*, const void*, void*, float*,
+                                 const int*, const int*, hipStream_t);
+template hipError_t fwd_bf16<64>(const AttnShape&, const void*, const void*, const void*, void*, float*,
+                                 const int*, const int*, hipStream_t);
+template hipError_t bwd_dq_bf16<32>(const AttnShape&, const void*, const void*, const void*, const void*,
+                                    const void*, const float*, void*, float*, const int*, const int*,
+                                    const int*, int, int4*, int2*, hipStream_t);
+template hipError_t bwd_dq_bf16<64>(const AttnShape&, const void*, const void*, const void*, const void*,
+                                    const void*, const float*, void*, float*, const int*, const int*,
+                                    const int*, int, int4*, int2*, hipStream_t);
+template hipError_t bwd_dkv_bf16<32>(const AttnShape&, const void*, const void*, const void*, const void*,
+                                     const float*, const float*, void*, void*, const int*, const int4*,
+                                     int, int, float*, hipStream_t);
+template hipError_t bwd_dkv_bf16<64>(const AttnShape&, const void*, const void*, const void*, const void*,
+                                     const float*, const float*, void*, void*, const int*, const int4*,
+                                     int, int, float*, hipStream_t);
+
+}  // namespace spion

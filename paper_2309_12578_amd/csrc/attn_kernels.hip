@@ -18,134 +18,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "attn_common.h"
 #include "spion_internal.h"
 
 namespace spion {
-
-typedef __bf16 bf16_t;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kD = 64;  // head dimension
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-
-// Per element type: a 16-byte lane fragment of EPL elements; four lane groups make a chunk of KC
-// contraction elements along d.
-template <typename T>
-struct Elem;
-template <>
-struct Elem<float> {
-    static constexpr int EPL = 4, KC = 16;
-    typedef f32x4 Frag;   // d-chunk fragment
-    typedef f32x4 Quad;   // 4 consecutive elements (one accumulator tile's worth per lane)
-};
-template <>
-struct Elem<bf16_t> {
-    static constexpr int EPL = 8, KC = 32;
-    typedef bf16x8 Frag;
-    typedef bf16x4 Quad;
-};
-
-// acc[16x16] += A(16 x KC) * B(KC x 16), both fragments indexed [lane % 16][chunk + (lane / 16) * EPL + e]
-__device__ __forceinline__ f32x4 mma_d(f32x4 acc, bf16x8 a, bf16x8 b) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
-}
-__device__ __forceinline__ f32x4 mma_d(f32x4 acc, f32x4 a, f32x4 b) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[i], acc, 0, 0, 0);
-    return acc;
-}
-// 16-deep contraction: lane group g holds contraction indices 4 g .. 4 g + 3
-__device__ __forceinline__ f32x4 mma_q(f32x4 acc, bf16x4 a, bf16x4 b) {
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a),
-                                                     __builtin_bit_cast(s16x4, b), acc, 0, 0, 0);
-}
-__device__ __forceinline__ f32x4 mma_q(f32x4 acc, f32x4 a, f32x4 b) { return mma_d(acc, a, b); }
-
-template <typename T>
-__device__ __forceinline__ typename Elem<T>::Quad to_quad(f32x4 v);
-template <>
-__device__ __forceinline__ f32x4 to_quad<float>(f32x4 v) {
-    return v;
-}
-template <>
-__device__ __forceinline__ bf16x4 to_quad<bf16_t>(f32x4 v) {
-    bf16x4 r;
-    r[0] = (bf16_t)v[0];
-    r[1] = (bf16_t)v[1];
-    r[2] = (bf16_t)v[2];
-    r[3] = (bf16_t)v[3];
-    return r;
-}
-__device__ __forceinline__ bf16x8 join(bf16x4 lo, bf16x4 hi) {
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-// acc[dt] += T^T(16 d-rows x keys) * X(keys x 16 owned rows) for dt = 0..3, where
-//   tl      transposed tile in LDS, [64][LDT], element (d, key)
-//   x[kt]   accumulator-layout tiles (16 keys each) already converted to the element type
-// i.e. out^T[d][owned] += sum_key tile[key][d] * x[key][owned].
-template <typename T, int BS, int LDT>
-__device__ __forceinline__ void mma_over_rows(f32x4 (&acc)[4], const T* tl,
-                                              const typename Elem<T>::Quad (&x)[BS / 16], int r, int g) {
-    typedef typename Elem<T>::Quad Quad;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-        const T* row = tl + (dt * 16 + r) * LDT + 4 * g;
-        if constexpr (sizeof(T) == 2 && BS >= 32) {
-#pragma unroll
-            for (int pc = 0; pc < BS / 32; ++pc) {
-                const bf16x4 lo = *reinterpret_cast<const bf16x4*>(row + pc * 32);
-                const bf16x4 hi = *reinterpret_cast<const bf16x4*>(row + pc * 32 + 16);
-                acc[dt] = mma_d(acc[dt], join(lo, hi), join(x[2 * pc], x[2 * pc + 1]));
-            }
-        } else {
-#pragma unroll
-            for (int kt = 0; kt < BS / 16; ++kt) {
-                const Quad a = *reinterpret_cast<const Quad*>(row + kt * 16);
-                acc[dt] = mma_q(acc[dt], a, x[kt]);
-            }
-        }
-    }
-}
-
-// Stage one bs x 64 tile (contiguous in global memory) into LDS: row-major into rm (if non-null
-// at compile time) and transposed into tr.
-template <typename T, int BS, int LDK, int LDT, bool ROWMAJOR, bool TRANSPOSED>
-__device__ __forceinline__ void stage_tile(const T* __restrict__ src, T* rm, T* tr, int tid) {
-    typedef typename Elem<T>::Frag Frag;
-    constexpr int EPL = Elem<T>::EPL;
-    constexpr int NT = BS * 4;
-    constexpr int FPR = kD / EPL;  // fragments per row
-#pragma unroll
-    for (int it = 0; it < (int)sizeof(T); ++it) {
-        const int idx = it * NT + tid;
-        const int row = idx / FPR, cc = idx % FPR;
-        const Frag f = *reinterpret_cast<const Frag*>(src + (size_t)idx * EPL);
-        if constexpr (ROWMAJOR) *reinterpret_cast<Frag*>(rm + row * LDK + cc * EPL) = f;
-        if constexpr (TRANSPOSED) {
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) tr[(cc * EPL + e) * LDT + row] = f[e];
-        }
-    }
-}
-
-__device__ __forceinline__ float group_max(float v) {
-    v = fmaxf(v, __shfl_xor(v, 16));
-    return fmaxf(v, __shfl_xor(v, 32));
-}
-__device__ __forceinline__ float group_sum(float v) {
-    v += __shfl_xor(v, 16);
-    return v + __shfl_xor(v, 32);
-}
-
-template <typename T>
-__device__ __forceinline__ void store_quad(T* dst, f32x4 v) {
-    *reinterpret_cast<typename Elem<T>::Quad*>(dst) = to_quad<T>(v);
-}
 
 // ------------------------------------------------------------------------------------------------
 // forward: workgroup = (head, block row I); wave w owns query rows I*bs + 16 w .. + 15
@@ -236,55 +112,6 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_kernel(
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) store_quad<T>(orow + dt * 16 + 4 * g, oacc[dt] * inv);
     if (g == 0) LSE[(size_t)bh * L + qrow] = lsum > 0.f ? (m + log2f(lsum)) * kLn2 : -INFINITY;
-}
-
-// ------------------------------------------------------------------------------------------------
-// Key-side work list.  Vertical stripes give block columns with up to nb kept rows next to columns
-// with one or two, so the key-side kernel does not take one column per workgroup: a column with cnt
-// kept rows is cut into nch = ceil(cnt / kChunk) near-equal chunks, each a work item.  A column with
-// one chunk writes dK / dV directly; the chunks of a longer column write fp32 partial tiles into
-// numbered slots that a second kernel adds up in chunk order (deterministic).  The list is the same
-// for every head; one wave of the query-side kernel (which always runs first) builds it.
-//   sched[w]   = {J, kb, ke, slot}: BSC entries [kb, ke) of column J; slot < 0: write final output;
-//                J < 0: unused work item
-//   colinfo[J] = {first slot, nch}
-// ------------------------------------------------------------------------------------------------
-constexpr int kChunk = 8;
-
-__host__ __device__ inline int key_work_items_max(int nnzb, int nb) { return nnzb / kChunk + nb; }
-__host__ __device__ inline int key_slots_max(int nnzb) { return 2 * (nnzb / kChunk) + 2; }
-
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(v, off);
-        if (lane >= off) v += o;
-    }
-    return v;
-}
-
-__device__ void build_key_schedule(const int* __restrict__ col_ptr, int nb, int w_max,
-                                   int4* __restrict__ sched, int2* __restrict__ colinfo, int lane) {
-    int run_w = 0, run_s = 0;
-    for (int base = 0; base < nb; base += 64) {
-        const int J = base + lane;
-        const bool valid = J < nb;
-        const int c0 = valid ? col_ptr[J] : 0;
-        const int cnt = valid ? col_ptr[J + 1] - c0 : 0;
-        const int nch = valid ? (cnt > kChunk ? (cnt + kChunk - 1) / kChunk : 1) : 0;
-        const int ns = nch > 1 ? nch : 0;
-        const int w_incl = wave_incl_scan(nch, lane), s_incl = wave_incl_scan(ns, lane);
-        const int w0 = run_w + w_incl - nch, s0 = run_s + s_incl - ns;
-        if (valid) {
-            colinfo[J] = make_int2(nch > 1 ? s0 : -1, nch);
-            for (int ci = 0; ci < nch && w0 + ci < w_max; ++ci)
-                sched[w0 + ci] = make_int4(J, c0 + (ci * cnt) / nch, c0 + ((ci + 1) * cnt) / nch,
-                                           nch > 1 ? s0 + ci : -1);
-        }
-        run_w += __shfl(w_incl, 63);
-        run_s += __shfl(s_incl, 63);
-    }
-    for (int w = run_w + lane; w < w_max; w += 64) sched[w] = make_int4(-1, 0, 0, -1);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -506,6 +333,7 @@ BwdWorkspace::BwdWorkspace(int BH, int L, int bs, int nb, int nnzb) {
 template <typename T, int BS>
 static hipError_t fwd_t(const AttnShape& s, const void* Q, const void* K, const void* V, void* O,
                         float* LSE, const int* row_ptr, const int* col_idx, hipStream_t st) {
+    if constexpr (sizeof(T) == 2 && BS >= 32) return fwd_bf16<BS>(s, Q, K, V, O, LSE, row_ptr, col_idx, st);
     attn_fwd_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), dim3(BS * 4), 0, st>>>(
         static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
         static_cast<T*>(O), LSE, row_ptr, col_idx, s.L, s.nb, s.scale * kLog2e, s.paper_denom);
@@ -524,7 +352,14 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
     int2* colinfo = reinterpret_cast<int2*>(base + ws.colinfo_off);
     float* partial = reinterpret_cast<float*>(base + ws.partial_off);
     const dim3 block(BS * 4);
-    if (s.bwd_phases & 1) {
+    constexpr bool kTuned = sizeof(T) == 2 && BS >= 32;
+    if constexpr (kTuned) {
+        if (s.bwd_phases & 1) {
+            const hipError_t e = bwd_dq_bf16<BS>(s, Q, K, V, O, dO, LSE, dQ, delta, row_ptr, col_idx, col_ptr,
+                                                 ws.w_max, sched, colinfo, st);
+            if (e != hipSuccess) return e;
+        }
+    } else if (s.bwd_phases & 1) {
         attn_bwd_dq_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
             static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
             static_cast<const T*>(O), static_cast<const T*>(dO), LSE, static_cast<T*>(dQ), delta,
@@ -533,12 +368,18 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
         if (e != hipSuccess) return e;
     }
     if (s.bwd_phases & 2) {
+        if constexpr (kTuned) {
+            const hipError_t e = bwd_dkv_bf16<BS>(s, Q, K, V, dO, LSE, delta, dK, dV, row_idx, sched, ws.w_max,
+                                                  ws.n_slots, partial, st);
+            if (e != hipSuccess) return e;
+        } else {
         attn_bwd_dkv_kernel<T, BS><<<dim3((unsigned)(ws.w_max * s.BH)), block, 0, st>>>(
             static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
             static_cast<const T*>(dO), LSE, delta, static_cast<T*>(dK), static_cast<T*>(dV), row_idx,
             sched, ws.w_max, ws.n_slots, partial, s.L, s.scale, s.scale * kLog2e);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+        }
         attn_bwd_dkv_reduce_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
             partial, colinfo, ws.n_slots, static_cast<T*>(dK), static_cast<T*>(dV), s.L, s.nb, s.scale);
     }

@@ -39,5 +39,19 @@ struct BwdWorkspace {
 };
 size_t attn_bwd_workspace_bytes(int BH, int L, int bs, int nb, int nnzb);
 
+// attn_bf16_kernels.hip: tuned bf16 kernels, BS in {32, 64}
+template <int BS>
+hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                    const int* row_ptr, const int* col_idx, hipStream_t st);
+template <int BS>
+hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
+                       const void* dO, const float* LSE, void* dQ, float* delta, const int* row_ptr,
+                       const int* col_idx, const int* col_ptr, int w_max, int4* sched, int2* colinfo,
+                       hipStream_t st);
+template <int BS>
+hipError_t bwd_dkv_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* dO,
+                        const float* LSE, const float* delta, void* dK, void* dV, const int* row_idx,
+                        const int4* sched, int w_max, int n_slots, float* partial, hipStream_t st);
+
 }  // namespace spion
 #endif
