@@ -35,6 +35,22 @@ def parse_args():
     return ap.parse_args()
 
 
+def read_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+    recorded in profiles/traffic_<workload>.txt (lines "kernel fetch_bytes write_bytes"); None if
+    no such measurement is on file."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % workload)
+    try:
+        with open(path) as fh:
+            for line in fh:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == kernel:
+                    return int(float(parts[1]) + float(parts[2]))
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -96,6 +112,13 @@ def main() -> int:
         return s
 
     sets = [make_set() for _ in range(max(args.sets, 1))]
+
+    # one plain device copy of known size: the yardstick that scales rocprofv3's FETCH_SIZE /
+    # WRITE_SIZE readings (see profiles/) into bytes
+    cal_src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device=dev).fill_(1)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    del cal_src, cal_dst
     code = sp.binding._dtype_code(tdt)
 
     def fwd(s):
@@ -154,6 +177,8 @@ def main() -> int:
     dom_tflops = acc.useful_flops(nnzb, w.block, w.d, BH, products=dom_products) / (kern_ms[dom] * 1e-3) / 1e12
     path_bytes = acc.algorithmic_bytes("path", BH, w.L, w.d, esz)
 
+    traffic = read_traffic(w.name, dom)
+
     out = {
         "metric": "sparse MHA fwd+bwd useful TFLOP/s (ms/layer in ms_per_step) at L=%d" % w.L,
         "value": round(tflops, 3),
@@ -172,7 +197,7 @@ def main() -> int:
                    "cache": "cold (rotating %d buffer sets, %.0f MB)" % (len(sets), len(sets) * 8 * acc.tensor_bytes(BH, w.L, w.d, esz) / 1e6)},
         "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(dom_gbps, 2),
                      "peak": acc.MI355X_HBM_GBPS, "unit": "GB/s",
-                     "frac": round(dom_gbps / acc.MI355X_HBM_GBPS, 5), "traffic": None,
+                     "frac": round(dom_gbps / acc.MI355X_HBM_GBPS, 5), "traffic": traffic,
                      "avg_kernel_ms": round(kern_ms[dom], 5), "algorithmic_bytes": dom_bytes},
         "roofline_mfma": {"kernel": dom, "achieved": round(dom_tflops, 3), "peak": peak_tf,
                           "unit": "TFLOP/s", "frac": round(dom_tflops / peak_tf, 5)},

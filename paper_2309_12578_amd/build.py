@@ -19,8 +19,10 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-
 SOURCES = [
     ("spion_api.hip", ["-ffp-contract=off"]),
     ("pattern_kernels.hip", ["-ffp-contract=off"]),
-    ("attn_kernels.hip", []),
-    ("attn_bf16_kernels.hip", []),
+    # MFMA accumulators in ordinary VGPRs: the softmax between two products reads them with VALU
+    # instructions, and the AGPR form costs a register copy per value per step
+    ("attn_kernels.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
+    ("attn_bf16_kernels.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
 ]
 
 

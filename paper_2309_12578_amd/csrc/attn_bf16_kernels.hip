@@ -16,6 +16,19 @@
 
 namespace spion {
 
+// Developer build only (-DSPION_KERNEL_TRACE): workgroup timestamps of pipeline stages, 16 slots per
+// workgroup, written to a buffer the test harness installs with hipMemcpyToSymbol.
+#ifdef SPION_KERNEL_TRACE
+__device__ long long* spion_trace_buf = nullptr;
+void set_trace_buf(long long* p) { (void)hipMemcpyToSymbol(HIP_SYMBOL(spion_trace_buf), &p, sizeof(p)); }
+#define SPION_TP(slot)                                                                          \
+    do {                                                                                        \
+        if (threadIdx.x == 0 && spion_trace_buf) spion_trace_buf[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); \
+    } while (0)
+#else
+#define SPION_TP(slot) do { } while (0)
+#endif
+
 constexpr int kLd = kD + 8;   // LDS row stride in bf16 elements (144 B: 16-byte aligned, bank-skewed)
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
@@ -69,6 +82,15 @@ __device__ __forceinline__ void mma_over_rows_tr(f32x4 (&acc)[4], const bf16_t* 
 }
 
 // ------------------------------------------------------------------------------------------------
+// LDS budget and pipeline.  A workgroup may use at most ~32 KB of LDS if four are to share a CU
+// (more than that and only three fit, which turns a one-round launch into two).  Of the two tiles a
+// step needs, the one that is read until the end of the step is double buffered and the one that is
+// only needed early is single buffered and refilled behind a mid-step barrier, while the MFMAs of the
+// second half run: 3 tiles of 9 KB.  Tile it+1 waits in registers during step it; its loads were
+// issued one step earlier, the block index it needs two steps earlier.
+// ------------------------------------------------------------------------------------------------
+
+// ------------------------------------------------------------------------------------------------
 // forward
 // ------------------------------------------------------------------------------------------------
 template <int BS>
@@ -78,7 +100,8 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     const int* __restrict__ col_idx, int L, int nb, int total, float scale_log2, int paper_denom) {
     constexpr int NKT = BS / 16;
     __shared__ __attribute__((aligned(16))) bf16_t k_s[2][BS * kLd];
-    __shared__ __attribute__((aligned(16))) bf16_t v_s[2][BS * kLd];
+    __shared__ __attribute__((aligned(16))) bf16_t v_s[BS * kLd];
+    SPION_TP(0);
 
     const int vid = xcd_remap(blockIdx.x, total);
     const int I = vid % nb, bh = vid / nb;
@@ -86,27 +109,34 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     const size_t head = (size_t)bh * L * kD;
     const int qrow = I * BS + wave * 16 + r;
     const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
+    const int last = n > 0 ? n - 1 : 0;
+    const int* cols = col_idx + jb;
+    // clamped reads stay inside this row's entries; an empty row reads nothing
+    const int J0 = n > 0 ? cols[0] : 0, J1 = n > 0 ? cols[1 < last ? 1 : last] : 0;
+    int Jpre = n > 0 ? cols[2 < last ? 2 : last] : 0;   // block index of tile it + 2
 
     TileRegs<BS> kreg, vreg;
-    if (n > 0) {
-        const size_t t0 = head + (size_t)col_idx[jb] * BS * kD;
-        kreg.load(K + t0, tid);
-        vreg.load(V + t0, tid);
+    {
+        TileRegs<BS> k0, v0;
+        if (n > 0) {
+            k0.load(K + head + (size_t)J0 * BS * kD, tid);
+            v0.load(V + head + (size_t)J0 * BS * kD, tid);
+        }
+        if (n > 1) {
+            kreg.load(K + head + (size_t)J1 * BS * kD, tid);
+            vreg.load(V + head + (size_t)J1 * BS * kD, tid);
+        }
+        if (n > 0) {
+            k0.store(k_s[0], tid);
+            v0.store(v_s, tid);
+        }
     }
     bf16x8 qf[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c)
         qf[c] = *reinterpret_cast<const bf16x8*>(Q + head + (size_t)qrow * kD + c * 32 + g * 8);
-    if (n > 0) {
-        kreg.store(k_s[0], tid);
-        vreg.store(v_s[0], tid);
-    }
-    if (n > 1) {
-        const size_t t1 = head + (size_t)col_idx[jb + 1] * BS * kD;
-        kreg.load(K + t1, tid);
-        vreg.load(V + t1, tid);
-    }
     __syncthreads();
+    SPION_TP(1);
 
     float m = -INFINITY, lsum = 0.f;   // m in log2 units (score * scale * log2 e)
     f32x4 oacc[4];
@@ -115,15 +145,10 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
 
     for (int it = 0; it < n; ++it) {
         const int buf = it & 1;
-        if (it + 1 < n) {   // tile it+1 has landed in registers during the previous multiply
-            kreg.store(k_s[buf ^ 1], tid);
-            vreg.store(v_s[buf ^ 1], tid);
-        }
-        if (it + 2 < n) {
-            const size_t t2 = head + (size_t)col_idx[jb + it + 2] * BS * kD;
-            kreg.load(K + t2, tid);
-            vreg.load(V + t2, tid);
-        }
+        const bool more = it + 1 < n, more2 = it + 2 < n;
+        const size_t t2 = head + (size_t)Jpre * BS * kD;
+        if (more) kreg.store(k_s[buf ^ 1], tid);
+        if (more2) kreg.load(K + t2, tid);
         const bf16_t* kt_s = k_s[buf];
         // S^T tile kt: [key 16 kt + 4 g + i][query r]
         f32x4 s[NKT];
@@ -157,8 +182,13 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
             pq[kt] = to_quad<bf16_t>(s[kt]);
         }
         m = m_new;
-        mma_over_rows_tr<BS>(oacc, v_s[buf], pq, r, g);   // O^T[d][query] += V^T P^T
-        __syncthreads();
+        if (it > 0) __syncthreads();                  // V tile of this step is in place
+        mma_over_rows_tr<BS>(oacc, v_s, pq, r, g);    // O^T[d][query] += V^T P^T
+        __syncthreads();                              // every wave is done with v_s and k_s[buf]
+        if (more) vreg.store(v_s, tid);
+        if (more2) vreg.load(V + t2, tid);
+        Jpre = cols[it + 3 < last ? it + 3 : last];
+        if (it < 12) SPION_TP(2 + it);
     }
 
     lsum = group_sum(lsum);
@@ -177,6 +207,7 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) store_quad<bf16_t>(orow + dt * 16 + 4 * g, oacc[dt] * inv);
     if (g == 0) LSE[(size_t)bh * L + qrow] = lsum > 0.f ? (m + log2f(lsum)) * kLn2 : -INFINITY;
+    SPION_TP(15);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -192,7 +223,8 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     float scale_log2) {
     constexpr int NKT = BS / 16;
     __shared__ __attribute__((aligned(16))) bf16_t k_s[2][BS * kLd];
-    __shared__ __attribute__((aligned(16))) bf16_t v_s[2][BS * kLd];
+    __shared__ __attribute__((aligned(16))) bf16_t v_s[BS * kLd];
+    SPION_TP(0);
 
     const int vid = xcd_remap(blockIdx.x, total);
     const int I = vid % nb, bh = vid / nb;
@@ -200,12 +232,27 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     const size_t head = (size_t)bh * L * kD;
     const int qrow = I * BS + wave * 16 + r;
     const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
+    const int last = n > 0 ? n - 1 : 0;
+    const int* cols = col_idx + jb;
+    // clamped reads stay inside this row's entries; an empty row reads nothing
+    const int J0 = n > 0 ? cols[0] : 0, J1 = n > 0 ? cols[1 < last ? 1 : last] : 0;
+    int Jpre = n > 0 ? cols[2 < last ? 2 : last] : 0;
 
     TileRegs<BS> kreg, vreg;
-    if (n > 0) {
-        const size_t t0 = head + (size_t)col_idx[jb] * BS * kD;
-        kreg.load(K + t0, tid);
-        vreg.load(V + t0, tid);
+    {
+        TileRegs<BS> k0, v0;
+        if (n > 0) {
+            k0.load(K + head + (size_t)J0 * BS * kD, tid);
+            v0.load(V + head + (size_t)J0 * BS * kD, tid);
+        }
+        if (n > 1) {
+            kreg.load(K + head + (size_t)J1 * BS * kD, tid);
+            vreg.load(V + head + (size_t)J1 * BS * kD, tid);
+        }
+        if (n > 0) {
+            k0.store(k_s[0], tid);
+            v0.store(v_s, tid);
+        }
     }
     if (vid == 0 && tid < 64) build_key_schedule(col_ptr, nb, w_max, sched, colinfo, tid);
 
@@ -223,16 +270,6 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     delta = group_sum(delta);
     if (g == 0) delta_out[(size_t)bh * L + qrow] = delta;
     const float lse2 = LSE[(size_t)bh * L + qrow] * kLog2e;
-
-    if (n > 0) {
-        kreg.store(k_s[0], tid);
-        vreg.store(v_s[0], tid);
-    }
-    if (n > 1) {
-        const size_t t1 = head + (size_t)col_idx[jb + 1] * BS * kD;
-        kreg.load(K + t1, tid);
-        vreg.load(V + t1, tid);
-    }
     __syncthreads();
 
     f32x4 dq[4];
@@ -241,15 +278,10 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
 
     for (int it = 0; it < n; ++it) {
         const int buf = it & 1;
-        if (it + 1 < n) {
-            kreg.store(k_s[buf ^ 1], tid);
-            vreg.store(v_s[buf ^ 1], tid);
-        }
-        if (it + 2 < n) {
-            const size_t t2 = head + (size_t)col_idx[jb + it + 2] * BS * kD;
-            kreg.load(K + t2, tid);
-            vreg.load(V + t2, tid);
-        }
+        const bool more = it + 1 < n, more2 = it + 2 < n;
+        const size_t t2 = head + (size_t)Jpre * BS * kD;
+        if (more) kreg.store(k_s[buf ^ 1], tid);
+        if (more2) kreg.load(K + t2, tid);
         bf16x4 dsq[NKT];
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
@@ -257,8 +289,8 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 const int off = (kt * 16 + r) * kLd + c * 32 + g * 8;
-                s = mma_d(s, *reinterpret_cast<const bf16x8*>(k_s[buf] + off), qf[c]);     // S^T = K Q^T
-                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(v_s[buf] + off), dof[c]);  // dP^T = V dO^T
+                s = mma_d(s, *reinterpret_cast<const bf16x8*>(k_s[buf] + off), qf[c]);   // S^T = K Q^T
+                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(v_s + off), dof[c]);     // dP^T = V dO^T
             }
             f32x4 ds;
 #pragma unroll
@@ -268,8 +300,12 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
             }
             dsq[kt] = to_quad<bf16_t>(ds);
         }
-        mma_over_rows_tr<BS>(dq, k_s[buf], dsq, r, g);   // dQ^T[d][query] += K^T dS^T
-        __syncthreads();
+        __syncthreads();                                  // every wave is done with v_s
+        if (more) vreg.store(v_s, tid);
+        if (more2) vreg.load(V + t2, tid);
+        mma_over_rows_tr<BS>(dq, k_s[buf], dsq, r, g);    // dQ^T[d][query] += K^T dS^T
+        Jpre = cols[it + 3 < last ? it + 3 : last];
+        __syncthreads();                                  // k_s[buf] free, next V and K tiles in place
     }
     bf16_t* drow = dQ + head + (size_t)qrow * kD;
 #pragma unroll
@@ -288,29 +324,52 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
     float scale, float scale_log2) {
     constexpr int NQT = BS / 16;
     __shared__ __attribute__((aligned(16))) bf16_t q_s[2][BS * kLd];
-    __shared__ __attribute__((aligned(16))) bf16_t do_s[2][BS * kLd];
+    __shared__ __attribute__((aligned(16))) bf16_t do_s[BS * kLd];
     __shared__ __attribute__((aligned(16))) float lse_s[2][BS];
     __shared__ __attribute__((aligned(16))) float delta_s[2][BS];
 
     const int vid = xcd_remap(blockIdx.x, total);
     const int w = vid % w_max, bh = vid / w_max;
     const int4 item = sched[w];
-    const int J = item.x, kb = item.y, n = item.z - item.y, slot = item.w;
+    const int J = item.x, n = item.z - item.y, slot = item.w;
     if (J < 0) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     const size_t head = (size_t)bh * L * kD;
     const size_t vec = (size_t)bh * L;
     const int krow = J * BS + wave * 16 + r;
+    const int last = n > 0 ? n - 1 : 0;
+    const int* rows = row_idx + item.y;
+    const int I0 = n > 0 ? rows[0] : 0, I1 = n > 0 ? rows[1 < last ? 1 : last] : 0;
+    int Ipre = n > 0 ? rows[2 < last ? 2 : last] : 0;
 
     TileRegs<BS> qreg, doreg;
     float lse_r = 0.f, delta_r = 0.f;
-    if (n > 0) {
-        const int I0 = row_idx[kb];
-        qreg.load(Q + head + (size_t)I0 * BS * kD, tid);
-        doreg.load(dO + head + (size_t)I0 * BS * kD, tid);
-        if (tid < BS) {
-            lse_r = LSE[vec + I0 * BS + tid];
-            delta_r = delta[vec + I0 * BS + tid];
+    {
+        TileRegs<BS> q0, do0;
+        float lse0 = 0.f, delta0 = 0.f;
+        if (n > 0) {
+            q0.load(Q + head + (size_t)I0 * BS * kD, tid);
+            do0.load(dO + head + (size_t)I0 * BS * kD, tid);
+            if (tid < BS) {
+                lse0 = LSE[vec + I0 * BS + tid];
+                delta0 = delta[vec + I0 * BS + tid];
+            }
+        }
+        if (n > 1) {
+            qreg.load(Q + head + (size_t)I1 * BS * kD, tid);
+            doreg.load(dO + head + (size_t)I1 * BS * kD, tid);
+            if (tid < BS) {
+                lse_r = LSE[vec + I1 * BS + tid];
+                delta_r = delta[vec + I1 * BS + tid];
+            }
+        }
+        if (n > 0) {
+            q0.store(q_s[0], tid);
+            do0.store(do_s, tid);
+            if (tid < BS) {
+                lse_s[0][tid] = lse0 * kLog2e;
+                delta_s[0][tid] = delta0;
+            }
         }
     }
     bf16x8 kf[2], vf[2];
@@ -319,23 +378,6 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
         const size_t off = head + (size_t)krow * kD + c * 32 + g * 8;
         kf[c] = *reinterpret_cast<const bf16x8*>(K + off);
         vf[c] = *reinterpret_cast<const bf16x8*>(V + off);
-    }
-    if (n > 0) {
-        qreg.store(q_s[0], tid);
-        doreg.store(do_s[0], tid);
-        if (tid < BS) {
-            lse_s[0][tid] = lse_r * kLog2e;
-            delta_s[0][tid] = delta_r;
-        }
-    }
-    if (n > 1) {
-        const int I1 = row_idx[kb + 1];
-        qreg.load(Q + head + (size_t)I1 * BS * kD, tid);
-        doreg.load(dO + head + (size_t)I1 * BS * kD, tid);
-        if (tid < BS) {
-            lse_r = LSE[vec + I1 * BS + tid];
-            delta_r = delta[vec + I1 * BS + tid];
-        }
     }
     __syncthreads();
 
@@ -348,21 +390,21 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
 
     for (int it = 0; it < n; ++it) {
         const int buf = it & 1;
-        if (it + 1 < n) {
+        const bool more = it + 1 < n, more2 = it + 2 < n;
+        const size_t t2 = head + (size_t)Ipre * BS * kD;
+        const size_t v2 = vec + (size_t)Ipre * BS + tid;
+        if (more) {
             qreg.store(q_s[buf ^ 1], tid);
-            doreg.store(do_s[buf ^ 1], tid);
             if (tid < BS) {
                 lse_s[buf ^ 1][tid] = lse_r * kLog2e;
                 delta_s[buf ^ 1][tid] = delta_r;
             }
         }
-        if (it + 2 < n) {
-            const int I2 = row_idx[kb + it + 2];
-            qreg.load(Q + head + (size_t)I2 * BS * kD, tid);
-            doreg.load(dO + head + (size_t)I2 * BS * kD, tid);
+        if (more2) {
+            qreg.load(Q + t2, tid);
             if (tid < BS) {
-                lse_r = LSE[vec + I2 * BS + tid];
-                delta_r = delta[vec + I2 * BS + tid];
+                lse_r = LSE[v2];
+                delta_r = delta[v2];
             }
         }
         bf16x4 pq[NQT], dsq[NQT];
@@ -372,8 +414,8 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 const int off = (qt * 16 + r) * kLd + c * 32 + g * 8;
-                s = mma_d(s, *reinterpret_cast<const bf16x8*>(q_s[buf] + off), kf[c]);     // S = Q K^T
-                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(do_s[buf] + off), vf[c]);  // dP = dO V^T
+                s = mma_d(s, *reinterpret_cast<const bf16x8*>(q_s[buf] + off), kf[c]);   // S = Q K^T
+                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(do_s + off), vf[c]);     // dP = dO V^T
             }
             const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&lse_s[buf][qt * 16 + 4 * g]);
             const f32x4 del4 = *reinterpret_cast<const f32x4*>(&delta_s[buf][qt * 16 + 4 * g]);
@@ -386,9 +428,13 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
             pq[qt] = to_quad<bf16_t>(p);
             dsq[qt] = to_quad<bf16_t>(ds);
         }
-        mma_over_rows_tr<BS>(dv, do_s[buf], pq, r, g);   // dV^T[d][key] += dO^T P
-        mma_over_rows_tr<BS>(dk, q_s[buf], dsq, r, g);   // dK^T[d][key] += Q^T dS
-        __syncthreads();
+        mma_over_rows_tr<BS>(dv, do_s, pq, r, g);          // dV^T[d][key] += dO^T P
+        __syncthreads();                                    // every wave is done with do_s
+        if (more) doreg.store(do_s, tid);
+        if (more2) doreg.load(dO + t2, tid);
+        mma_over_rows_tr<BS>(dk, q_s[buf], dsq, r, g);      // dK^T[d][key] += Q^T dS
+        Ipre = rows[it + 3 < last ? it + 3 : last];
+        __syncthreads();                                    // q_s[buf] free, next tiles in place
     }
     if (slot < 0) {
         bf16_t* dkrow = dK + head + (size_t)krow * kD;
@@ -399,6 +445,9 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
             store_quad<bf16_t>(dvrow + dt * 16 + 4 * g, dv[dt]);
         }
     } else {
+        // fp32 partial tile of this chunk, unscaled: [head][slot][dK | dV][bs][64]; a second kernel
+        // adds the chunks of a column in chunk order (a kernel boundary is the cheapest way to make
+        // the tiles visible across XCDs: a device-scope release inside the kernel flushes the whole L2)
         float* pk = partial + ((size_t)bh * n_slots + slot) * (2 * BS * kD) + (size_t)(wave * 16 + r) * kD;
         float* pv = pk + BS * kD;
 #pragma unroll

@@ -288,27 +288,27 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_kernel(
 }
 
 // Adds the partial tiles of every block column that was cut into several chunks, in chunk order.
-// workgroup = (head, block column J); thread t owns float4 number t, t + NT, ... of the tile.
+// One thread per float4 of the bs x 64 output tile: workgroup = (head, block column J, part), 256
+// threads, bs / 16 parts per tile.
 template <typename T, int BS>
-__global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_reduce_kernel(
+__global__ __launch_bounds__(256) void attn_bwd_dkv_reduce_kernel(
     const float* __restrict__ partial, const int2* __restrict__ colinfo, int n_slots, T* __restrict__ dK,
     T* __restrict__ dV, int L, int nb, float scale) {
-    const int J = blockIdx.x % nb, bh = blockIdx.x / nb;
+    constexpr int PARTS = BS / 16;
+    const int part = blockIdx.x % PARTS, J = (blockIdx.x / PARTS) % nb, bh = blockIdx.x / (PARTS * nb);
     const int2 info = colinfo[J];
     if (info.y <= 1) return;
-    constexpr int NT = BS * 4, NV = BS * kD / 4;
-    const float* base = partial + ((size_t)bh * n_slots + info.x) * (2 * BS * kD);
-    const size_t out0 = (size_t)bh * L * kD + (size_t)J * BS * kD;
-    for (int v = threadIdx.x; v < NV; v += NT) {
-        f32x4 ak = f32x4{0.f, 0.f, 0.f, 0.f}, av = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < info.y; ++c) {
-            const float* pk = base + (size_t)c * (2 * BS * kD);
-            ak += *reinterpret_cast<const f32x4*>(pk + v * 4);
-            av += *reinterpret_cast<const f32x4*>(pk + BS * kD + v * 4);
-        }
-        store_quad<T>(dK + out0 + v * 4, ak * scale);
-        store_quad<T>(dV + out0 + v * 4, av);
+    const int v = part * 256 + threadIdx.x;
+    const float* pk = partial + ((size_t)bh * n_slots + info.x) * (2 * BS * kD) + v * 4;
+    f32x4 ak = f32x4{0.f, 0.f, 0.f, 0.f}, av = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int c = 0; c < info.y; ++c) {
+        ak += *reinterpret_cast<const f32x4*>(pk + (size_t)c * (2 * BS * kD));
+        av += *reinterpret_cast<const f32x4*>(pk + (size_t)c * (2 * BS * kD) + BS * kD);
     }
+    const size_t out = (size_t)bh * L * kD + (size_t)J * BS * kD + v * 4;
+    store_quad<T>(dK + out, ak * scale);
+    store_quad<T>(dV + out, av);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -380,7 +380,7 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         }
-        attn_bwd_dkv_reduce_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
+        attn_bwd_dkv_reduce_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH * (BS / 16))), dim3(256), 0, st>>>(
             partial, colinfo, ws.n_slots, static_cast<T*>(dK), static_cast<T*>(dV), s.L, s.nb, s.scale);
     }
     return hipGetLastError();
