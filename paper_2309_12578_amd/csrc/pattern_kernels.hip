@@ -17,6 +17,20 @@
 
 namespace spion {
 
+// Developer build only (-DSPION_KERNEL_TRACE): timestamps of the stages of pattern_finish_kernel.
+#ifdef SPION_KERNEL_TRACE
+__device__ long long* spion_pattern_trace_buf = nullptr;
+void set_pattern_trace_buf(long long* p) {
+    (void)hipMemcpyToSymbol(HIP_SYMBOL(spion_pattern_trace_buf), &p, sizeof(p));
+}
+#define SPION_PTP(slot)                                                                        \
+    do {                                                                                       \
+        if (threadIdx.x == 0 && spion_pattern_trace_buf) spion_pattern_trace_buf[slot] = wall_clock64(); \
+    } while (0)
+#else
+#define SPION_PTP(slot) do { } while (0)
+#endif
+
 // ------------------------------------------------------------------------------------------------
 // conv + pool
 // ------------------------------------------------------------------------------------------------
@@ -46,92 +60,73 @@ __device__ __forceinline__ int isect(int lo_a, int hi_a, int lo_b, int hi_b) {
 __device__ __forceinline__ long long shfl_xor_i64(long long v, int mask) { return __shfl_xor(v, mask); }
 
 // slots: 0 (0,0)  1 (-1,0)  2 (+1,0)  3 (0,-1)  4 (0,+1)  5 (-1,-1)  6 (+1,+1)  7 unused
-// grid.x = nb * nb input blocks; block = 64 * min(4, (bs/16)^2) threads; wave w walks the 16 x 16
-// sub-tiles w, w + nwaves, ... of the block, one float4 per lane per sub-tile.
-__global__ __launch_bounds__(256) void conv_pool_kernel(const float* __restrict__ A, int L, int bs, int p,
-                                                        unsigned long long* __restrict__ pool) {
-    const int nb = L / bs;
+// grid.x = nb * nb input blocks; block = 64 * min(4, (BS/16)^2) threads; wave w walks the 16 x 16
+// sub-tiles w, w + nwaves, ... of the block, one float4 per lane per sub-tile.  Which neighbours a
+// sub-tile can reach is uniform over the wave, so the edge work is skipped with scalar branches.
+template <int BS>
+__global__ __launch_bounds__(BS >= 32 ? 256 : 64) void conv_pool_kernel(
+    const float* __restrict__ A, int L, int p, unsigned long long* __restrict__ pool) {
+    constexpr int NSD = BS / 16, NSUB = NSD * NSD, NW = NSUB < 4 ? NSUB : 4, KSUB = NSUB / NW;
+    const int nb = L / BS;
     const int I = blockIdx.x / nb, J = blockIdx.x % nb;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    const int nsd = bs >> 4, nsub = nsd * nsd;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lr = lane >> 2, lc = (lane & 3) << 2;
-    const float* base = A + (size_t)I * bs * L + (size_t)J * bs;
+    const float* base = A + (size_t)I * BS * L + (size_t)J * BS;
 
-    constexpr int kMaxSub = 4;   // sub-tiles per wave: (64/16)^2 / 4
-    float4 a4[kMaxSub];
+    float4 a4[KSUB];
 #pragma unroll
-    for (int k = 0; k < kMaxSub; ++k) {
-        const int st = wave + k * nwaves;
-        if (st < nsub) {
-            const int u = (st / nsd) * 16 + lr, v0 = (st % nsd) * 16 + lc;
-            a4[k] = *reinterpret_cast<const float4*>(base + (size_t)u * L + v0);
-        }
+    for (int k = 0; k < KSUB; ++k) {
+        const int st = wave + k * NW;
+        const int u = (st / NSD) * 16 + lr, v0 = (st % NSD) * 16 + lc;
+        a4[k] = *reinterpret_cast<const float4*>(base + (size_t)u * L + v0);
     }
 
     long long tot[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long s_all = 0;
 #pragma unroll
-    for (int k = 0; k < kMaxSub; ++k) {
-        const int st = wave + k * nwaves;
-        if (st >= nsub) break;
-        const int su = (st / nsd) * 16, sv = (st % nsd) * 16;
+    for (int k = 0; k < KSUB; ++k) {
+        const int st = wave + k * NW;
+        const int su = (st / NSD) * 16, sv = (st % NSD) * 16;
         const int u = su + lr, v0 = sv + lc;
-        // wave-uniform: which neighbours can this sub-tile reach at all
-        const bool top = su < p, bottom = su + 15 > bs - 1 - p;
-        const bool left = sv < p, right = sv + 15 > bs - 1 - p;
+        const bool top = su < p, bottom = su + 15 > BS - 1 - p;
+        const bool left = sv < p, right = sv + 15 > BS - 1 - p;
         const int rm_lo = u + 1, rm_hi = p;
-        const int r0_lo = (u - bs + 1) > -p ? (u - bs + 1) : -p, r0_hi = u < p ? u : p;
-        const int rp_lo = -p, rp_hi = u - bs;
+        const int r0_lo = (u - BS + 1) > -p ? (u - BS + 1) : -p, r0_hi = u < p ? u : p;
+        const int rp_lo = -p, rp_hi = u - BS;
         const float av[4] = {a4[k].x, a4[k].y, a4[k].z, a4[k].w};
+        int hi[4], lo[4], c0_lo[4], c0_hi[4];
         int s_hi = 0, s_lo = 0;
-        int n_hi[7] = {0, 0, 0, 0, 0, 0, 0}, n_lo[7] = {0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int v = v0 + e;
             const float x = av[e] * 1048576.0f;
             const float xf = floorf(x);
-            const int hi = (int)xf;
-            const int lo = (int)rintf((x - xf) * 1048576.0f);
-            s_hi += hi;
-            s_lo += lo;
-            const int cm_lo = v + 1, cm_hi = p;
-            const int c0_lo = (v - bs + 1) > -p ? (v - bs + 1) : -p, c0_hi = v < p ? v : p;
-            const int cp_lo = -p, cp_hi = v - bs;
-            if (top) {
-                const int w = isect(rm_lo, rm_hi, c0_lo, c0_hi);
-                n_hi[1] += w * hi;
-                n_lo[1] += w * lo;
-            }
-            if (bottom) {
-                const int w = isect(rp_lo, rp_hi, c0_lo, c0_hi);
-                n_hi[2] += w * hi;
-                n_lo[2] += w * lo;
-            }
-            if (left) {
-                const int w = isect(r0_lo, r0_hi, cm_lo, cm_hi);
-                n_hi[3] += w * hi;
-                n_lo[3] += w * lo;
-            }
-            if (right) {
-                const int w = isect(r0_lo, r0_hi, cp_lo, cp_hi);
-                n_hi[4] += w * hi;
-                n_lo[4] += w * lo;
-            }
-            if (top && left) {
-                const int w = isect(rm_lo, rm_hi, cm_lo, cm_hi);
-                n_hi[5] += w * hi;
-                n_lo[5] += w * lo;
-            }
-            if (bottom && right) {
-                const int w = isect(rp_lo, rp_hi, cp_lo, cp_hi);
-                n_hi[6] += w * hi;
-                n_lo[6] += w * lo;
-            }
+            hi[e] = (int)xf;
+            lo[e] = (int)rintf((x - xf) * 1048576.0f);
+            s_hi += hi[e];
+            s_lo += lo[e];
+            c0_lo[e] = (v - BS + 1) > -p ? (v - BS + 1) : -p;
+            c0_hi[e] = v < p ? v : p;
         }
-        // 4 elements * weight (< 128) * 2^21 fits 32 bits; widen once per sub-tile
         s_all += ((long long)s_hi << 20) + s_lo;
+        // weights < 128 and |hi|, lo <= 2^20: 24-bit multiplies, 4 terms fit 32 bits
+        auto edge = [&](int slot, auto weight) {
+            int n_hi = 0, n_lo = 0;
 #pragma unroll
-        for (int t = 1; t < 7; ++t) tot[t] += ((long long)n_hi[t] << 20) + n_lo[t];
+            for (int e = 0; e < 4; ++e) {
+                const int w = weight(e);
+                n_hi += __mul24(w, hi[e]);
+                n_lo += __mul24(w, lo[e]);
+            }
+            tot[slot] += ((long long)n_hi << 20) + n_lo;
+        };
+        if (top) edge(1, [&](int e) { return isect(rm_lo, rm_hi, c0_lo[e], c0_hi[e]); });
+        if (bottom) edge(2, [&](int e) { return isect(rp_lo, rp_hi, c0_lo[e], c0_hi[e]); });
+        if (left) edge(3, [&](int e) { return isect(r0_lo, r0_hi, v0 + e + 1, p); });
+        if (right) edge(4, [&](int e) { return isect(r0_lo, r0_hi, -p, v0 + e - BS); });
+        if (top && left) edge(5, [&](int e) { return isect(rm_lo, rm_hi, v0 + e + 1, p); });
+        if (bottom && right) edge(6, [&](int e) { return isect(rp_lo, rp_hi, -p, v0 + e - BS); });
     }
     long long others = 0;
 #pragma unroll
@@ -252,10 +247,10 @@ __device__ __forceinline__ int wave_compact(const uint8_t* f, int stride, int nb
 
 // mode: 0 = threshold given in t_abs, 1 = quantile rank k_rank, 2 = mean + kval * std.
 // mask_g / expd_g / pos: scratch arrays of nb*nb entries in global memory; when use_lds is set the
-// two byte arrays live in dynamic LDS instead (2 * nb * nb bytes).
+// byte arrays live in dynamic LDS instead (3 * nb * nb bytes).  mask_g holds 2 * nb * nb bytes.
 __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     const long long* __restrict__ pool, int nb, int mode, long long k_rank, double kval, double t_abs,
-    int no_fill, int use_lds, uint8_t* mask_g, uint8_t* expd_g, int* __restrict__ pos,
+    int no_fill, int use_lds, uint8_t* mask_g, uint8_t* expd_g, int* pos,
     uint8_t* __restrict__ fl, int* __restrict__ row_ptr, int* __restrict__ col_idx,
     int* __restrict__ col_ptr, int* __restrict__ row_idx, int* __restrict__ bsr_pos,
     int* __restrict__ nnzb_out) {
@@ -264,38 +259,96 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     const long long n = (long long)nb * nb;
     uint8_t* mask = use_lds ? dyn_lds : mask_g;
     uint8_t* expd = use_lds ? dyn_lds + n : expd_g;
+    uint8_t* mask_t = use_lds ? dyn_lds + 2 * n : mask_g + n;   // final mask, transposed (step 5)
+    if (use_lds > 1) pos = reinterpret_cast<int*>(dyn_lds + 4 * n);   // 3n rounded up to a multiple of 4
     __shared__ unsigned hist[256];
     __shared__ Thresh th;
     __shared__ unsigned long long sel_prefix;
     __shared__ long long sel_k;
     __shared__ int scan_scratch[kFinishWaves + 1];
     __shared__ int line_start[SPION_MAX_NB_INTERNAL];
+    __shared__ int col_start[SPION_MAX_NB_INTERNAL];
+    // nb <= 64 only: successor bits of row r in anti-diagonal order, skew[r][s] = bits of cell
+    // (r, s - r), zero where s - r is outside the row; and the "reached" bit of every cell as one
+    // 128-bit mask per row in the same order
+    __shared__ __attribute__((aligned(16))) uint8_t skew[64 * 128];
+    __shared__ unsigned rbits[64 * 4];
+    const bool small = nb <= 64;
+    if (small)
+        for (int i = tid; i < 64 * 128 / 4; i += kFinishThreads) reinterpret_cast<unsigned*>(skew)[i] = 0u;
 
+    SPION_PTP(0);
     // ---- 1. threshold ------------------------------------------------------------------------
     if (mode == 1) {
-        // exact k-th smallest (0-based): most-significant-byte-first radix selection
+        // exact k-th smallest (0-based): most-significant-byte-first radix selection.  Up to
+        // kCached values per thread stay in registers across the 8 passes (covers nb <= 64).
+        constexpr int kCached = 4;
+        const bool cached = n <= (long long)kCached * kFinishThreads;
+        unsigned long long key[kCached];
+#pragma unroll
+        for (int j = 0; j < kCached; ++j) {
+            const long long i = (long long)j * kFinishThreads + tid;
+            key[j] = (cached && i < n) ? ((unsigned long long)pool[i] ^ 0x8000000000000000ull) : 0ull;
+        }
         if (tid == 0) {
             sel_prefix = 0ull;
             sel_k = k_rank;
         }
+        if (tid < 256) hist[tid] = 0u;
+        __syncthreads();
+        auto count = [&](unsigned long long u, bool in_range, int pass, unsigned long long prefix) {
+            const int shift = pass * 8;
+            const bool match = in_range && ((pass == 7) || ((u >> (shift + 8)) == (prefix >> (shift + 8))));
+            const unsigned byte = (unsigned)((u >> shift) & 0xFFull);
+            // the leading bytes are usually equal for the whole wave: one atomic instead of 64
+            const unsigned long long m = __ballot(match);
+            if (m == 0ull) return;
+            const unsigned first = __shfl(byte, __ffsll((long long)m) - 1);
+            if (__ballot(match && byte == first) == m) {
+                if (lane == 0) atomicAdd(&hist[first], (unsigned)__popcll(m));
+            } else if (match) {
+                atomicAdd(&hist[byte], 1u);
+            }
+        };
         for (int pass = 7; pass >= 0; --pass) {
             const int shift = pass * 8;
-            if (tid < 256) hist[tid] = 0u;
-            __syncthreads();
             const unsigned long long prefix = sel_prefix;
             const long long k = sel_k;
-            for (long long i = tid; i < n; i += kFinishThreads) {
-                const unsigned long long u = (unsigned long long)pool[i] ^ 0x8000000000000000ull;
-                const bool match = (pass == 7) || ((u >> (shift + 8)) == (prefix >> (shift + 8)));
-                if (match) atomicAdd(&hist[(unsigned)((u >> shift) & 0xFFull)], 1u);
+            if (cached) {
+#pragma unroll
+                for (int j = 0; j < kCached; ++j)
+                    count(key[j], (long long)j * kFinishThreads + tid < n, pass, prefix);
+            } else {
+                for (long long base = 0; base < n; base += kFinishThreads) {
+                    const long long i = base + tid;
+                    const unsigned long long u =
+                        i < n ? ((unsigned long long)pool[i] ^ 0x8000000000000000ull) : 0ull;
+                    count(u, i < n, pass, prefix);
+                }
             }
             __syncthreads();
-            // the bin b with excl(b) <= k < incl(b): found by a 256-wide scan
-            int c = tid < 256 ? (int)hist[tid] : 0, total = 0;
-            const int excl = block_exclusive_scan(c, &total, scan_scratch);
-            if (tid < 256 && c > 0 && k >= excl && k < (long long)excl + c) {
-                sel_k = k - excl;
-                sel_prefix = prefix | ((unsigned long long)tid << shift);
+            // wave 0 finds the bin b with excl(b) <= k < incl(b); 4 bins per lane
+            if (wave == 0) {
+                unsigned c[4];
+                int s4 = 0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    c[q] = hist[4 * lane + q];
+                    s4 += (int)c[q];
+                }
+                const int incl = wave_inclusive_scan(s4, lane);
+                long long e = incl - s4;
+                if (k >= e && k < incl) {
+                    int q = 0;
+                    while (k >= e + (long long)c[q]) {
+                        e += c[q];
+                        ++q;
+                    }
+                    sel_k = k - e;
+                    sel_prefix = prefix | ((unsigned long long)(4 * lane + q) << shift);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) hist[4 * lane + q] = 0u;
             }
             __syncthreads();
         }
@@ -332,6 +385,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     }
     __syncthreads();
     const Thresh t = th;
+    SPION_PTP(1);
 
     // ---- 2. per cell: successor bits (which of down / right / diag equal their maximum), the
     //         "above threshold" bit, and the seed flag (first row and first column) ------------------
@@ -346,37 +400,49 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
             m |= (dn == mx ? kDown : 0u) | (rt == mx ? kRight : 0u) | (dg == mx ? kDiag : 0u);
         }
         mask[i] = (uint8_t)m;
+        if (small) skew[r * 128 + r + c] = (uint8_t)(m & 7u);
         expd[i] = no_fill ? (uint8_t)kReached : ((r == 0 || c == 0) ? (uint8_t)kExpanded : (uint8_t)0);
     }
     __syncthreads();
 
+    SPION_PTP(2);
     // ---- 3. fill: every move raises r + c, so anti-diagonal s depends only on s-1 and s-2.  A cell is
     //         reached iff an expanded predecessor lists it as a successor; reached cells are expanded
     //         in turn whether or not they exceed the threshold. -------------------------------------
     if (!no_fill) {
-        if (nb <= 64) {
-            // one wave, lane = row; the outgoing successor bits of the previous two anti-diagonals
-            // travel in registers, the neighbour row's bits arrive by a one-lane shift
+        if (small) {
+            // One wave, lane = row r.  The row's successor bits sit in 32 registers in anti-diagonal
+            // order, so level s reads a compile-time register; the outgoing bits of the previous
+            // two levels travel in registers and the neighbour row's bits arrive by a one-lane
+            // shift.  Cells outside the matrix have no bits and can neither be reached nor expand.
             if (wave == 0) {
                 const int r = lane;
+                unsigned sk[32];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const uint4 v = reinterpret_cast<const uint4*>(skew + r * 128)[q];
+                    sk[4 * q] = v.x;
+                    sk[4 * q + 1] = v.y;
+                    sk[4 * q + 2] = v.z;
+                    sk[4 * q + 3] = v.w;
+                }
                 unsigned out1 = 0u, out2 = 0u;
-                unsigned m_next = (r == 0) ? mask[0] : 0u;
-                for (int s = 0; s <= 2 * nb - 2; ++s) {
-                    const int c = s - r;
-                    const bool valid = r < nb && c >= 0 && c < nb;
-                    const unsigned m = m_next;
-                    const int c1 = c + 1;   // prefetch the next anti-diagonal's bits
-                    m_next = (r < nb && c1 >= 0 && c1 < nb) ? mask[(long long)r * nb + c1] : 0u;
+                unsigned rb[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int s = 0; s < 127; ++s) {
+                    const unsigned m = (sk[s >> 2] >> (8 * (s & 3))) & 7u;
                     const unsigned both = out1 | (out2 << 8);
                     const unsigned up = __builtin_amdgcn_update_dpp(0u, both, 0x138 /* wave_shr:1 */,
                                                                     0xf, 0xf, false);
-                    const bool reached =
-                        valid && ((out1 & kRight) || (up & kDown) || ((up >> 8) & kDiag));
-                    const bool expanded = valid && (reached || r == 0 || c == 0);
-                    if (reached) expd[(long long)r * nb + c] = (uint8_t)(kExpanded | kReached);
+                    const unsigned hit = (out1 & kRight) | (up & kDown) | ((up >> 8) & kDiag);
+                    const bool reached = hit != 0u;
+                    const bool expanded = reached || r == 0 || s == r;   // seeds: row 0, column 0
+                    rb[s >> 5] |= (reached ? 1u : 0u) << (s & 31);
                     out2 = out1;
-                    out1 = expanded ? (m & 7u) : 0u;
+                    out1 = expanded ? m : 0u;
                 }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) rbits[r * 4 + q] = rb[q];
             }
         } else {
             for (int s = 1; s <= 2 * nb - 2; ++s) {
@@ -395,63 +461,84 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
         }
     }
     __syncthreads();
+    SPION_PTP(3);
     // ---- 4. fl_out = reached and above the threshold, or on the diagonal; kept in expd for step 5 ---
     for (long long i = tid; i < n; i += kFinishThreads) {
         const int r = (int)(i / nb), c = (int)(i % nb);
-        const uint8_t f = (((expd[i] & kReached) && (mask[i] & kAbove)) || r == c) ? 1 : 0;
+        const bool reached = (small && !no_fill) ? ((rbits[r * 4 + ((r + c) >> 5)] >> ((r + c) & 31)) & 1u) != 0u
+                                                 : (expd[i] & kReached) != 0;
+        const uint8_t f = ((reached && (mask[i] & kAbove)) || r == c) ? 1 : 0;
         fl[i] = f;
         mask[i] = f;
+        mask_t[(long long)c * nb + r] = f;
     }
     __syncthreads();
 
-    // ---- 5. compaction: BSR (rows), then BSC (columns); one wave per row / column ------------------
-    int total = 0;
-    {
-        int cnt = 0;
-        for (int r = wave; r < nb; r += kFinishWaves) {
-            const int k = wave_compact<false>(mask + (long long)r * nb, 1, nb, lane, 0, nullptr, nullptr, 0,
-                                              0, nullptr);
-            if (lane == 0) line_start[r] = k;
+    SPION_PTP(4);
+    // ---- 5. compaction: BSR (rows) and BSC (columns); one wave per row / column -------------------
+    const bool want_bsc = col_ptr != nullptr;
+    for (int r = wave; r < nb; r += kFinishWaves) {
+        const int k = wave_compact<false>(mask + (long long)r * nb, 1, nb, lane, 0, nullptr, nullptr, 0, 0,
+                                          nullptr);
+        if (lane == 0) line_start[r] = k;
+        if (want_bsc) {
+            const int kc = wave_compact<false>(mask_t + (long long)r * nb, 1, nb, lane, 0, nullptr, nullptr,
+                                               0, 0, nullptr);
+            if (lane == 0) col_start[r] = kc;
         }
-        __syncthreads();
-        for (int base = 0; base < nb; base += kFinishThreads) {   // nb <= 1024: one round
-            cnt = (base + tid < nb) ? line_start[base + tid] : 0;
-            const int start = block_exclusive_scan(cnt, &total, scan_scratch);
-            if (base + tid < nb) {
-                line_start[base + tid] = start;
-                row_ptr[base + tid] = start;
+    }
+    __syncthreads();
+    if (small) {
+        // nb <= 64: one wave scans the row counts, another the column counts
+        if (wave < 2 && (wave == 0 || want_bsc)) {
+            int* start = wave == 0 ? line_start : col_start;
+            int* ptr = wave == 0 ? row_ptr : col_ptr;
+            const int v = lane < nb ? start[lane] : 0;
+            const int incl = wave_inclusive_scan(v, lane);
+            if (lane < nb) {
+                start[lane] = incl - v;
+                ptr[lane] = incl - v;
+            }
+            if (lane == 63) {
+                ptr[nb] = incl;
+                if (wave == 0) *nnzb_out = incl;
             }
         }
         __syncthreads();
-        for (int r = wave; r < nb; r += kFinishWaves)
-            wave_compact<true>(mask + (long long)r * nb, 1, nb, lane, line_start[r], col_idx, pos,
-                               (long long)r * nb, 1, nullptr);
+    } else {
+        int total = 0;
+        int cnt = tid < nb ? line_start[tid] : 0;   // nb <= 1024 == kFinishThreads
+        int start = block_exclusive_scan(cnt, &total, scan_scratch);
+        if (tid < nb) {
+            line_start[tid] = start;
+            row_ptr[tid] = start;
+        }
         if (tid == 0) {
             row_ptr[nb] = total;
             *nnzb_out = total;
         }
-    }
-    if (col_ptr != nullptr) {
-        __syncthreads();
-        for (int c = wave; c < nb; c += kFinishWaves) {
-            const int k = wave_compact<false>(mask + c, nb, nb, lane, 0, nullptr, nullptr, 0, 0, nullptr);
-            if (lane == 0) line_start[c] = k;
-        }
-        __syncthreads();
-        for (int base = 0; base < nb; base += kFinishThreads) {
-            const int cnt = (base + tid < nb) ? line_start[base + tid] : 0;
-            const int start = block_exclusive_scan(cnt, &total, scan_scratch);
-            if (base + tid < nb) {
-                line_start[base + tid] = start;
-                col_ptr[base + tid] = start;
+        if (want_bsc) {
+            cnt = tid < nb ? col_start[tid] : 0;
+            start = block_exclusive_scan(cnt, &total, scan_scratch);
+            if (tid < nb) {
+                col_start[tid] = start;
+                col_ptr[tid] = start;
             }
+            if (tid == 0) col_ptr[nb] = total;
         }
         __syncthreads();
-        for (int c = wave; c < nb; c += kFinishWaves)
-            wave_compact<true>(mask + c, nb, nb, lane, line_start[c], row_idx, pos, (long long)c, nb,
-                               bsr_pos);
-        if (tid == 0) col_ptr[nb] = total;
     }
+    for (int r = wave; r < nb; r += kFinishWaves)
+        wave_compact<true>(mask + (long long)r * nb, 1, nb, lane, line_start[r], col_idx, pos,
+                           (long long)r * nb, 1, nullptr);
+    SPION_PTP(5);
+    if (want_bsc) {
+        __syncthreads();   // pos[] of every kept cell is written
+        for (int c = wave; c < nb; c += kFinishWaves)
+            wave_compact<true>(mask_t + (long long)c * nb, 1, nb, lane, col_start[c], row_idx, pos,
+                               (long long)c, nb, bsr_pos);
+    }
+    SPION_PTP(6);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -462,10 +549,13 @@ hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* poo
     const size_t n = (size_t)nb * nb;
     zero_u64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(
         reinterpret_cast<unsigned long long*>(pool), n);
-    const int nsub = (bs / 16) * (bs / 16);
-    const int threads = 64 * (nsub < 4 ? nsub : 4);
-    conv_pool_kernel<<<dim3((unsigned)n), dim3(threads), 0, st>>>(
-        A, L, bs, p, reinterpret_cast<unsigned long long*>(pool));
+    unsigned long long* out = reinterpret_cast<unsigned long long*>(pool);
+    if (bs == 16)
+        conv_pool_kernel<16><<<dim3((unsigned)n), dim3(64), 0, st>>>(A, L, p, out);
+    else if (bs == 32)
+        conv_pool_kernel<32><<<dim3((unsigned)n), dim3(256), 0, st>>>(A, L, p, out);
+    else
+        conv_pool_kernel<64><<<dim3((unsigned)n), dim3(256), 0, st>>>(A, L, p, out);
     return hipGetLastError();
 }
 
@@ -474,8 +564,11 @@ hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long l
                                  uint8_t* fl, int* row_ptr, int* col_idx, int* col_ptr, int* row_idx,
                                  int* bsr_pos, int* nnzb, hipStream_t st) {
     const size_t n = (size_t)nb * nb;
-    const int use_lds = 2 * n <= 48 * 1024 ? 1 : 0;   // keeps static + dynamic LDS under 64 KB
-    pattern_finish_kernel<<<dim3(1), dim3(kFinishThreads), use_lds ? 2 * n : 0, st>>>(
+    // keep static (~19 KB) + dynamic LDS under 64 KB: the three byte arrays if 3n fits, and the
+    // position array (4n more, placed at offset 4n) if 8n fits as well
+    const int use_lds = 8 * n <= 40 * 1024 ? 2 : (3 * n <= 40 * 1024 ? 1 : 0);
+    const size_t dyn = use_lds == 2 ? 8 * n : (use_lds == 1 ? 3 * n : 0);
+    pattern_finish_kernel<<<dim3(1), dim3(kFinishThreads), dyn, st>>>(
         pool, nb, mode, k_rank, kval, t_abs, no_fill, use_lds, mask, expd, pos, fl, row_ptr, col_idx,
         col_ptr, row_idx, bsr_pos, nnzb);
     return hipGetLastError();

@@ -25,7 +25,7 @@ struct PatternWs {
     explicit PatternWs(size_t n) {
         pool_off = 0;
         mask_off = pool_off + align_up(n * sizeof(int64_t));
-        expd_off = mask_off + align_up(n);
+        expd_off = mask_off + align_up(2 * n);   // cell bits, then the transposed final mask
         pos_off = expd_off + align_up(n);
         total = pos_off + align_up(n * sizeof(int32_t));
     }
