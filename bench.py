@@ -1,14 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the SPION sparse-attention path on one MI355X.
 
-A step is one forward + backward pass of the block-sparse attention of one layer (SDDMM, row
-softmax, SpMM and their gradients) on the L = 4096 workload, using the pattern that
-spion_pattern produced for that layer; pattern generation happens once per layer in the method and
-is timed separately.  Inputs are synthetic (seeded) and already resident in HBM; the step rotates
-through several buffer sets larger than the 256 MB Infinity Cache so that every step streams its
-tensors from HBM ("cold"); the same loop on a single buffer set ("warm") is reported next to it.
+A step is one forward + backward pass of the block-sparse attention (SDDMM, row softmax, SpMM and
+their gradients) of every layer of the workload, each with the pattern that spion_pattern produced
+for it; pattern generation happens once per layer in the method and is timed separately.  Inputs
+are synthetic (seeded) and already resident in HBM.  The step rotates through several buffer sets,
+together larger than the 256 MB Infinity Cache, so that every step streams its tensors from HBM
+("cold", the headline); the same loop on one buffer set ("warm") is reported next to it.
 
-Prints ONE JSON line (see the design doc for the fields).
+Default workload: cfg4_bf16_L4096 (B=4, H=4, L=4096, d=64, bf16, block 64), the configuration the
+metric is quoted on.  `--workload cfg5` runs the 4-layer stack and reports the per-layer imbalance.
+
+Prints ONE JSON line: metric / value / ms_per_step for the whole step; `roofline` (achieved
+algorithmic GB/s of the longest kernel phase against the HBM peak, with measured traffic when a
+profile is on file) and `roofline_mfma`; `path` (whole-step fractions, warm timing); `layers`
+(per-layer kernel times); `pattern` (spion_pattern timing); `cpu_baseline` (the CPU oracle).
 """
 from __future__ import annotations
 
@@ -22,14 +28,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+KERNELS = ("fwd", "bwd_query", "bwd_key")
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg4_bf16_L4096")
-    ap.add_argument("--sets", type=int, default=6, help="rotating buffer sets (cold-cache timing)")
+    ap.add_argument("--workload", default="cfg4_bf16_L4096",
+                    help="a workload name from spion_inputs.WORKLOADS, or cfg5 for the 4-layer stack")
+    ap.add_argument("--sets", type=int, default=0,
+                    help="rotating buffer sets per layer (0: enough to exceed the Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pattern-iters", type=int, default=20)
     return ap.parse_args()
@@ -70,48 +80,60 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
-    w = si.workload(args.workload)
-    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    esz = 4 if w.dtype == "f32" else 2
-    BH = w.B * w.H
+    if args.workload == "cfg5":
+        layers = [si.workload(5, l) for l in range(4)]
+        wl_name = "cfg5_4layer_bf16_L4096"
+    else:
+        layers = [si.workload(args.workload)]
+        wl_name = layers[0].name
+    w0 = layers[0]
+    tdt = torch.float32 if w0.dtype == "f32" else torch.bfloat16
+    esz = 4 if w0.dtype == "f32" else 2
+    code = sp.binding._dtype_code(tdt)
+    BH = w0.B * w0.H
+    set_bytes = 8 * acc.tensor_bytes(BH, w0.L, w0.d, esz)
+    n_sets = args.sets if args.sets > 0 else max(2, -(-400_000_000 // (set_bytes * len(layers))))
 
-    # ---------------------------------------------------------------- inputs
-    Q, K, V, dO = si.make_qkv_do(w)
-    A = si.make_score_map(w, Q, K)
-    A_dev = torch.from_numpy(A).to(dev)
-
-    # ---------------------------------------------------------------- pattern (timed separately)
-    pat = sp.generate_pattern(A_dev, w.block, w.filt, w.thresh_mode, w.thresh_value)
-    ws_pat = torch.empty(sp.spion_pattern_workspace_bytes(w.L, w.block), dtype=torch.uint8, device=dev)
     flush = torch.empty(512 * 1024 * 1024, dtype=torch.uint8, device=dev)
-    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.pattern_iters)]
-    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.pattern_iters)]
-    for i in range(args.pattern_iters):
-        flush.fill_(i & 1)          # evict A^s from the caches: the map comes straight from training
-        ev0[i].record()
-        sp.generate_pattern(A_dev, w.block, w.filt, w.thresh_mode, w.thresh_value, sync=False, out=pat,
-                            workspace=ws_pat)
-        ev1[i].record()
-    torch.cuda.synchronize()
-    pat_ms = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
-    pattern_ms = pat_ms[len(pat_ms) // 2]
+
+    # ---------------------------------------------------------------- per layer: inputs, pattern, buffers
+    class Layer:
+        pass
+
+    prepared = []
+    for w in layers:
+        ly = Layer()
+        ly.w = w
+        ly.Q, ly.K, ly.V, ly.dO = si.make_qkv_do(w)
+        ly.A = si.make_score_map(w, ly.Q, ly.K)
+        A_dev = torch.from_numpy(ly.A).to(dev)
+        ly.pat = sp.generate_pattern(A_dev, w.block, w.filt, w.thresh_mode, w.thresh_value)
+        ws_pat = torch.empty(sp.spion_pattern_workspace_bytes(w.L, w.block), dtype=torch.uint8, device=dev)
+        ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.pattern_iters)]
+        ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.pattern_iters)]
+        for i in range(args.pattern_iters):
+            flush.fill_(i & 1)      # evict A^s from the caches: the map comes straight from training
+            ev0[i].record()
+            sp.generate_pattern(A_dev, w.block, w.filt, w.thresh_mode, w.thresh_value, sync=False,
+                                out=ly.pat, workspace=ws_pat)
+            ev1[i].record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
+        ly.pattern_ms, ly.pattern_min_ms = ms[len(ms) // 2], ms[0]
+        ly.nnzb = ly.pat.nnzb
+        ly.density = ly.nnzb / float(w.nb * w.nb)
+        ly.sets = []
+        for _ in range(n_sets):
+            q, k, v, do = [torch.from_numpy(t).to(dev).to(tdt).view(w.B, w.H, w.L, w.d).contiguous()
+                           for t in (ly.Q, ly.K, ly.V, ly.dO)]
+            s = dict(q=q, k=k, v=v, do=do, O=torch.empty_like(q), dQ=torch.empty_like(q),
+                     dK=torch.empty_like(q), dV=torch.empty_like(q),
+                     LSE=torch.empty((w.B, w.H, w.L), dtype=torch.float32, device=dev))
+            nbytes = sp.spion_attn_workspace_bytes(w.B, w.H, w.L, w.d, w.block, code, ly.nnzb, True)
+            s["ws"] = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+            ly.sets.append(s)
+        prepared.append(ly)
     del flush
-    nnzb = pat.nnzb
-    density = nnzb / float(w.nb * w.nb)
-
-    # ---------------------------------------------------------------- buffer sets
-    def make_set():
-        q, k, v, do = [torch.from_numpy(t).to(dev).to(tdt).view(w.B, w.H, w.L, w.d).contiguous()
-                       for t in (Q, K, V, dO)]
-        s = dict(q=q, k=k, v=v, do=do, O=torch.empty_like(q), dQ=torch.empty_like(q),
-                 dK=torch.empty_like(q), dV=torch.empty_like(q),
-                 LSE=torch.empty((w.B, w.H, w.L), dtype=torch.float32, device=dev))
-        nbytes = sp.spion_attn_workspace_bytes(w.B, w.H, w.L, w.d, w.block, sp.binding._dtype_code(tdt),
-                                               nnzb, True)
-        s["ws"] = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
-        return s
-
-    sets = [make_set() for _ in range(max(args.sets, 1))]
 
     # one plain device copy of known size: the yardstick that scales rocprofv3's FETCH_SIZE /
     # WRITE_SIZE readings (see profiles/) into bytes
@@ -119,68 +141,79 @@ def main() -> int:
     cal_dst = torch.empty_like(cal_src)
     cal_dst.copy_(cal_src)
     del cal_src, cal_dst
-    code = sp.binding._dtype_code(tdt)
 
-    def fwd(s):
-        sp.spion_attn_fwd(s["q"], s["k"], s["v"], s["O"], s["LSE"], pat.row_ptr, pat.col_idx, nnzb,
-                          w.B, w.H, w.L, w.d, w.block, code)
+    def fwd(ly, s):
+        w = ly.w
+        sp.spion_attn_fwd(s["q"], s["k"], s["v"], s["O"], s["LSE"], ly.pat.row_ptr, ly.pat.col_idx,
+                          ly.nnzb, w.B, w.H, w.L, w.d, w.block, code)
 
-    def bwd(s, flags=0):
+    def bwd(ly, s, flags=0):
+        w = ly.w
         sp.spion_attn_bwd(s["q"], s["k"], s["v"], s["O"], s["do"], s["LSE"], s["dQ"], s["dK"], s["dV"],
-                          pat.row_ptr, pat.col_idx, pat.col_ptr, pat.row_idx, pat.bsr_pos, nnzb,
-                          w.B, w.H, w.L, w.d, w.block, code, flags=flags, workspace=s["ws"])
+                          ly.pat.row_ptr, ly.pat.col_idx, ly.pat.col_ptr, ly.pat.row_idx, ly.pat.bsr_pos,
+                          ly.nnzb, w.B, w.H, w.L, w.d, w.block, code, flags=flags, workspace=s["ws"])
 
-    def run(n_steps, use_sets):
+    def run(n_steps, rotate):
         for i in range(n_steps):
-            s = use_sets[i % len(use_sets)]
-            fwd(s)
-            bwd(s)
+            for ly in prepared:
+                fwd(ly, ly.sets[i % n_sets if rotate else 0])
+            for ly in reversed(prepared):
+                bwd(ly, ly.sets[i % n_sets if rotate else 0])
 
-    def timed(n_steps, use_sets):
+    def timed(n_steps, rotate):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        run(n_steps, use_sets)
+        run(n_steps, rotate)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n_steps
 
     # ---------------------------------------------------------------- headline: cold, rotating sets
-    run(args.warmup, sets)
-    ms_cold = timed(args.steps, sets)
-    # warm: one buffer set, tensors stay in the Infinity Cache between steps
-    run(args.warmup, sets[:1])
-    ms_warm = timed(args.steps, sets[:1])
+    run(args.warmup, True)
+    ms_cold = timed(args.steps, True)
+    run(args.warmup, False)
+    ms_warm = timed(args.steps, False)
 
-    # ---------------------------------------------------------------- per-kernel durations (events)
-    names = ("fwd", "bwd_query", "bwd_key")
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    for i in range(args.steps):
-        s = sets[i % len(sets)]
-        evs[i][0].record()
-        fwd(s)
-        evs[i][1].record()
-        bwd(s, sp.SPION_ATTN_BWD_QUERY_SIDE_ONLY)
-        evs[i][2].record()
-        bwd(s, sp.SPION_ATTN_BWD_KEY_SIDE_ONLY)
-        evs[i][3].record()
-    torch.cuda.synchronize()
-    kern_ms = {n: float(np.mean([e[j].elapsed_time(e[j + 1]) for e in evs])) for j, n in enumerate(names)}
+    # ---------------------------------------------------------------- per-kernel durations (HIP events on
+    # the launch stream, which is torch's current stream), per layer
+    per_layer = []
+    for ly in prepared:
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for i in range(args.steps):
+            s = ly.sets[i % n_sets]
+            evs[i][0].record()
+            fwd(ly, s)
+            evs[i][1].record()
+            bwd(ly, s, sp.SPION_ATTN_BWD_QUERY_SIDE_ONLY)
+            evs[i][2].record()
+            bwd(ly, s, sp.SPION_ATTN_BWD_KEY_SIDE_ONLY)
+            evs[i][3].record()
+        torch.cuda.synchronize()
+        km = {n: float(np.mean([e[j].elapsed_time(e[j + 1]) for e in evs])) for j, n in enumerate(KERNELS)}
+        fl = acc.useful_flops(ly.nnzb, ly.w.block, ly.w.d, BH, products=6)
+        tot = sum(km.values())
+        per_layer.append({"layer": ly.w.layer, "nnzb": ly.nnzb, "block_density": round(ly.density, 5),
+                          "kernel_ms": {k: round(v, 5) for k, v in km.items()},
+                          "ms": round(tot, 5), "tflops": round(fl / (tot * 1e-3) / 1e12, 3),
+                          "pattern_ms": round(ly.pattern_ms, 5), "useful_flop": fl})
 
     # ---------------------------------------------------------------- accounting
-    flops_step = acc.useful_flops(nnzb, w.block, w.d, BH, products=6)
+    flops_step = sum(p["useful_flop"] for p in per_layer)
     tflops = flops_step / (ms_cold * 1e-3) / 1e12
-    peak_tf = acc.MI355X_MFMA_TFLOPS[w.dtype]
-    dom = max(kern_ms, key=kern_ms.get)
-    dom_bytes = acc.algorithmic_bytes(dom, BH, w.L, w.d, esz)
-    dom_gbps = dom_bytes / (kern_ms[dom] * 1e-3) / 1e9
-    dom_products = {"fwd": 2, "bwd_query": 2, "bwd_key": 2}[dom]
-    dom_tflops = acc.useful_flops(nnzb, w.block, w.d, BH, products=dom_products) / (kern_ms[dom] * 1e-3) / 1e12
-    path_bytes = acc.algorithmic_bytes("path", BH, w.L, w.d, esz)
-
-    traffic = read_traffic(w.name, dom)
+    peak_tf = acc.MI355X_MFMA_TFLOPS[w0.dtype]
+    # dominant kernel: the one with the largest summed duration over the layers; roofline on the
+    # layer where it is longest
+    dom = max(KERNELS, key=lambda k: sum(p["kernel_ms"][k] for p in per_layer))
+    dom_layer = max(per_layer, key=lambda p: p["kernel_ms"][dom])
+    dom_ms = dom_layer["kernel_ms"][dom]
+    dom_bytes = acc.algorithmic_bytes(dom, BH, w0.L, w0.d, esz)
+    dom_gbps = dom_bytes / (dom_ms * 1e-3) / 1e9
+    dom_tflops = acc.useful_flops(dom_layer["nnzb"], w0.block, w0.d, BH, products=2) / (dom_ms * 1e-3) / 1e12
+    path_bytes = acc.algorithmic_bytes("path", BH, w0.L, w0.d, esz) * len(prepared)
+    dom_wl = layers[dom_layer["layer"]].name if len(layers) > 1 else wl_name
 
     out = {
-        "metric": "sparse MHA fwd+bwd useful TFLOP/s (ms/layer in ms_per_step) at L=%d" % w.L,
+        "metric": "sparse MHA fwd+bwd useful TFLOP/s (ms per step = ms/layer x layers) at L=%d" % w0.L,
         "value": round(tflops, 3),
         "unit": "TFLOP/s",
         "n_gpus": 1,
@@ -190,42 +223,56 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": w.dtype,
+        "dtype": w0.dtype,
         "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "H": w.H, "L": w.L, "d": w.d, "block": w.block,
-                   "filter": w.filt, "nnzb": nnzb, "block_density": round(density, 5),
-                   "cache": "cold (rotating %d buffer sets, %.0f MB)" % (len(sets), len(sets) * 8 * acc.tensor_bytes(BH, w.L, w.d, esz) / 1e6)},
-        "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(dom_gbps, 2),
+        "config": {"workload": wl_name, "layers": len(prepared), "B": w0.B, "H": w0.H, "L": w0.L, "d": w0.d,
+                   "block": w0.block, "filter": w0.filt,
+                   "nnzb": [p["nnzb"] for p in per_layer] if len(per_layer) > 1 else per_layer[0]["nnzb"],
+                   "block_density": [p["block_density"] for p in per_layer] if len(per_layer) > 1
+                   else per_layer[0]["block_density"],
+                   "cache": "cold (rotating %d buffer sets per layer, %.0f MB in total)"
+                            % (n_sets, n_sets * len(prepared) * set_bytes / 1e6)},
+        "roofline": {"kernel": dom, "workload": dom_wl, "bound": "hbm", "achieved": round(dom_gbps, 2),
                      "peak": acc.MI355X_HBM_GBPS, "unit": "GB/s",
-                     "frac": round(dom_gbps / acc.MI355X_HBM_GBPS, 5), "traffic": traffic,
-                     "avg_kernel_ms": round(kern_ms[dom], 5), "algorithmic_bytes": dom_bytes},
+                     "frac": round(dom_gbps / acc.MI355X_HBM_GBPS, 5), "traffic": read_traffic(dom_wl, dom),
+                     "avg_kernel_ms": round(dom_ms, 5), "algorithmic_bytes": dom_bytes},
         "roofline_mfma": {"kernel": dom, "achieved": round(dom_tflops, 3), "peak": peak_tf,
                           "unit": "TFLOP/s", "frac": round(dom_tflops / peak_tf, 5)},
         "path": {"useful_flop": flops_step, "mfma_frac": round(tflops / peak_tf, 5),
+                 "ms_per_layer": round(ms_cold / len(prepared), 5),
                  "algorithmic_bytes": path_bytes,
                  "hbm_GBps": round(path_bytes / (ms_cold * 1e-3) / 1e9, 2),
                  "hbm_frac": round(path_bytes / (ms_cold * 1e-3) / 1e9 / acc.MI355X_HBM_GBPS, 5),
                  "ms_per_step_warm": round(ms_warm, 5),
                  "tflops_warm": round(flops_step / (ms_warm * 1e-3) / 1e12, 3),
-                 "kernel_ms": {k: round(v, 5) for k, v in kern_ms.items()},
-                 "paper_ops_sparse_fwd_per_head": acc.paper_ops_sparse(w.L, w.d, nnzb * w.block * w.block)},
-        "pattern": {"ms": round(pattern_ms, 5), "min_ms": round(pat_ms[0], 5),
-                    "A_s_bytes": 4 * w.L * w.L,
-                    "GBps_whole_call": round(4 * w.L * w.L / (pattern_ms * 1e-3) / 1e9, 2)},
+                 "paper_ops_sparse_fwd_per_head": [acc.paper_ops_sparse(w0.L, w0.d, p["nnzb"] * w0.block ** 2)
+                                                   for p in per_layer]},
+        "layers": [{k: v for k, v in p.items() if k != "useful_flop"} for p in per_layer],
+        "pattern": {"ms": round(sum(ly.pattern_ms for ly in prepared), 5),
+                    "A_s_bytes": 4 * w0.L * w0.L * len(prepared),
+                    "GBps_whole_call": round(4 * w0.L * w0.L * len(prepared)
+                                             / (sum(ly.pattern_ms for ly in prepared) * 1e-3) / 1e9, 2)},
     }
+    if len(per_layer) > 1:
+        lm = [p["ms"] for p in per_layer]
+        out["imbalance"] = {"layer_ms_max_over_min": round(max(lm) / min(lm), 3),
+                            "density_max_over_min": round(max(p["block_density"] for p in per_layer)
+                                                          / min(p["block_density"] for p in per_layer), 3)}
 
-    # ---------------------------------------------------------------- CPU baseline: the oracle as is
+    # ---------------------------------------------------------------- CPU baseline: the oracle as it is
     if not args.no_cpu_baseline:
         import oracle
         nthr = oracle.threads()
+        ly = prepared[-1] if len(prepared) > 1 else prepared[0]
+        w = ly.w
         n_heads = min(BH, max(nthr, 1))
         t0 = time.perf_counter()
-        ref = oracle.generate_pattern(A, w.block, w.filt, w.thresh_mode, w.thresh_value)
+        ref = oracle.generate_pattern(ly.A, w.block, w.filt, w.thresh_mode, w.thresh_value)
         t_pat = time.perf_counter() - t0
         P = oracle.upsample(ref["fl_out"], w.block)
         t0 = time.perf_counter()
-        oracle.attn_fwd(Q[:n_heads], K[:n_heads], V[:n_heads], P)
-        oracle.attn_bwd(Q[:n_heads], K[:n_heads], V[:n_heads], dO[:n_heads], P)
+        oracle.attn_fwd(ly.Q[:n_heads], ly.K[:n_heads], ly.V[:n_heads], P)
+        oracle.attn_bwd(ly.Q[:n_heads], ly.K[:n_heads], ly.V[:n_heads], ly.dO[:n_heads], P)
         t_attn = time.perf_counter() - t0
         cpu_tf = acc.useful_flops(ref["nnzb"], w.block, w.d, n_heads, products=6) / t_attn / 1e12
         out["cpu_baseline"] = {
@@ -235,7 +282,7 @@ def main() -> int:
                       % (n_heads, BH, w.name, t_attn, t_pat),
             "pattern_s": round(t_pat, 3)}
         out["pattern"]["mask_matches_oracle"] = bool(
-            np.array_equal(ref["fl_out"], pat.fl_out.cpu().numpy()))
+            np.array_equal(ref["fl_out"], ly.pat.fl_out.cpu().numpy()))
     print(json.dumps(out))
     return 0
 
