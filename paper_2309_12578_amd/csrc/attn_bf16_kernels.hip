@@ -29,7 +29,11 @@ void set_trace_buf(long long* p) { (void)hipMemcpyToSymbol(HIP_SYMBOL(spion_trac
 #define SPION_TP(slot) do { } while (0)
 #endif
 
-constexpr int kLd = kD + 8;   // LDS row stride in bf16 elements (144 B: 16-byte aligned, bank-skewed)
+// LDS row stride in bf16 elements: 160 B.  Measured with SQ_LDS_BANK_CONFLICT: a 144 B stride costs
+// 38-42 % extra LDS cycles (the transpose reads fetch 32 B from each of 8 consecutive rows, which
+// tile the 64 banks only if the stride is an odd multiple of 32 B); 160 B has no conflicts for the
+// 16-byte fragment reads, the transpose reads and the staging writes alike.
+constexpr int kLd = kD + 16;
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
     typedef bf16x4 __attribute__((address_space(3))) * lds_ptr;
@@ -86,7 +90,7 @@ __device__ __forceinline__ void mma_over_rows_tr(f32x4 (&acc)[4], const bf16_t* 
 // (more than that and only three fit, which turns a one-round launch into two).  Of the two tiles a
 // step needs, the one that is read until the end of the step is double buffered and the one that is
 // only needed early is single buffered and refilled behind a mid-step barrier, while the MFMAs of the
-// second half run: 3 tiles of 9 KB.  Tile it+1 waits in registers during step it; its loads were
+// second half run: 3 tiles of 10 KB.  Tile it+1 waits in registers during step it; its loads were
 // issued one step earlier, the block index it needs two steps earlier.
 // ------------------------------------------------------------------------------------------------
 
@@ -138,10 +142,14 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     __syncthreads();
     SPION_TP(1);
 
-    float m = -INFINITY, lsum = 0.f;   // m in log2 units (score * scale * log2 e)
+    float m = -INFINITY;   // running row maximum in log2 units (score * scale * log2 e)
+    f32x4 lacc = f32x4{0.f, 0.f, 0.f, 0.f};   // running row sum, replicated in its 4 elements
     f32x4 oacc[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)1.0f;
 
     for (int it = 0; it < n; ++it) {
         const int buf = it & 1;
@@ -166,21 +174,23 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         }
         mx = group_max(mx);
         const float m_new = fmaxf(m, mx * scale_log2);
-        const float alpha = fast_exp2(m - m_new);
-        lsum *= alpha;
+        if (__any(m_new > m)) {   // some row's running maximum moved: rescale what is accumulated
+            const float alpha = fast_exp2(m - m_new);
+            lacc *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
+            for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
+        }
         bf16x4 pq[NKT];
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float p = fast_exp2(fmaf(s[kt][i], scale_log2, -m_new));
-                s[kt][i] = p;
-                lsum += p;
-            }
+            for (int i = 0; i < 4; ++i) s[kt][i] = fast_exp2(fmaf(s[kt][i], scale_log2, -m_new));
             pq[kt] = to_quad<bf16_t>(s[kt]);
         }
+        // row sums on the MFMA pipe: a tile of ones times P^T adds up each owned row's probabilities
+        // (the bf16 values that also enter P V), every accumulator element holding the same sum
+#pragma unroll
+        for (int pc = 0; pc < BS / 32; ++pc) lacc = mma_d(lacc, ones, join(pq[2 * pc], pq[2 * pc + 1]));
         m = m_new;
         if (it > 0) __syncthreads();                  // V tile of this step is in place
         mma_over_rows_tr<BS>(oacc, v_s, pq, r, g);    // O^T[d][query] += V^T P^T
@@ -191,7 +201,7 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         if (it < 12) SPION_TP(2 + it);
     }
 
-    lsum = group_sum(lsum);
+    float lsum = lacc[0];
     if (paper_denom) {
         // Algorithm 6: every masked entry of the row counts as a score of 0
         const float masked = (float)(L - n * BS);
