@@ -228,8 +228,8 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, const float* __restrict__ LSE,
     bf16_t* __restrict__ dQ, float* __restrict__ delta_out, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, const int* __restrict__ col_ptr, int w_max,
-    int4* __restrict__ sched, int2* __restrict__ colinfo, int L, int nb, int total, float scale,
+    const int* __restrict__ col_idx, const int* __restrict__ col_ptr, int w_max, int split_max,
+    int4* __restrict__ sched, int4* __restrict__ split, int L, int nb, int total, float scale,
     float scale_log2) {
     constexpr int NKT = BS / 16;
     __shared__ __attribute__((aligned(16))) bf16_t k_s[2][BS * kLd];
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
             v0.store(v_s, tid);
         }
     }
-    if (vid == 0 && tid < 64) build_key_schedule(col_ptr, nb, w_max, sched, colinfo, tid);
+    if (vid == 0 && tid < 64) build_key_schedule(col_ptr, nb, w_max, split_max, sched, split, tid);
 
     bf16x8 qf[2], dof[2];
     float delta = 0.f;
@@ -484,13 +484,14 @@ hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void
 template <int BS>
 hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
                        const void* dO, const float* LSE, void* dQ, float* delta, const int* row_ptr,
-                       const int* col_idx, const int* col_ptr, int w_max, int4* sched, int2* colinfo,
-                       hipStream_t st) {
+                       const int* col_idx, const int* col_ptr, int w_max, int split_max, int4* sched,
+                       int4* split, hipStream_t st) {
     const int total = s.nb * s.BH;
     attn_bwd_dq_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
         static_cast<const bf16_t*>(O), static_cast<const bf16_t*>(dO), LSE, static_cast<bf16_t*>(dQ), delta,
-        row_ptr, col_idx, col_ptr, w_max, sched, colinfo, s.L, s.nb, total, s.scale, s.scale * kLog2e);
+        row_ptr, col_idx, col_ptr, w_max, split_max, sched, split, s.L, s.nb, total, s.scale,
+        s.scale * kLog2e);
     return hipGetLastError();
 }
 
@@ -512,10 +513,10 @@ template hipError_t fwd_bf16<64>(const AttnShape&, const void*, const void*, con
                                  const int*, const int*, hipStream_t);
 template hipError_t bwd_dq_bf16<32>(const AttnShape&, const void*, const void*, const void*, const void*,
                                     const void*, const float*, void*, float*, const int*, const int*,
-                                    const int*, int, int4*, int2*, hipStream_t);
+                                    const int*, int, int, int4*, int4*, hipStream_t);
 template hipError_t bwd_dq_bf16<64>(const AttnShape&, const void*, const void*, const void*, const void*,
                                     const void*, const float*, void*, float*, const int*, const int*,
-                                    const int*, int, int4*, int2*, hipStream_t);
+                                    const int*, int, int, int4*, int4*, hipStream_t);
 template hipError_t bwd_dkv_bf16<32>(const AttnShape&, const void*, const void*, const void*, const void*,
                                      const float*, const float*, void*, void*, const int*, const int4*,
                                      int, int, float*, hipStream_t);

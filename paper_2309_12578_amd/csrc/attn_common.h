@@ -142,7 +142,7 @@ __device__ __forceinline__ void store_quad(T* dst, f32x4 v) {
 // for every head; one wave of the query-side kernel (which always runs first) builds it.
 //   sched[w]   = {J, kb, ke, slot}: BSC entries [kb, ke) of column J; slot < 0: write final output;
 //                J < 0: unused work item
-//   colinfo[J] = {first slot, nch}
+//   split[m]   = {J, first slot, nch, 0} for the m-th split column; J < 0: unused entry
 // ------------------------------------------------------------------------------------------------
 #ifndef SPION_KEY_CHUNK
 #define SPION_KEY_CHUNK 8   // kept rows per key-side work item (build-time tunable)
@@ -151,6 +151,7 @@ constexpr int kChunk = SPION_KEY_CHUNK;
 
 __host__ __device__ inline int key_work_items_max(int nnzb, int nb) { return nnzb / kChunk + nb; }
 __host__ __device__ inline int key_slots_max(int nnzb) { return 2 * (nnzb / kChunk) + 2; }
+__host__ __device__ inline int key_split_max(int nnzb) { return nnzb / (kChunk + 1) + 1; }
 
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 #pragma unroll
@@ -161,11 +162,11 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
     return v;
 }
 
-__device__ void build_key_schedule(const int* __restrict__ col_ptr, int nb, int w_max,
-                                   int4* __restrict__ sched, int2* __restrict__ colinfo, int lane) {
+__device__ void build_key_schedule(const int* __restrict__ col_ptr, int nb, int w_max, int split_max,
+                                   int4* __restrict__ sched, int4* __restrict__ split, int lane) {
     // Two passes: the chunks of split columns (the longest work items) get the lowest work item
     // numbers and so start first; columns that fit one work item follow.
-    int run_w = 0, run_s = 0;
+    int run_w = 0, run_s = 0, run_m = 0;
     for (int pass = 0; pass < 2; ++pass) {
         for (int base = 0; base < nb; base += 64) {
             const int J = base + lane;
@@ -175,22 +176,24 @@ __device__ void build_key_schedule(const int* __restrict__ col_ptr, int nb, int 
             const int nch_all = valid ? (cnt > kChunk ? (cnt + kChunk - 1) / kChunk : 1) : 0;
             const bool mine = valid && ((nch_all > 1) == (pass == 0));
             const int nch = mine ? nch_all : 0;
-            const int ns = nch > 1 ? nch : 0;
+            const int ns = nch > 1 ? nch : 0, is_split = nch > 1 ? 1 : 0;
             const int w_incl = wave_incl_scan(nch, lane), s_incl = wave_incl_scan(ns, lane);
-            const int w0 = run_w + w_incl - nch, s0 = run_s + s_incl - ns;
+            const int m_incl = wave_incl_scan(is_split, lane);
+            const int w0 = run_w + w_incl - nch, s0 = run_s + s_incl - ns, m0 = run_m + m_incl - is_split;
             if (mine) {
-                colinfo[J] = make_int2(nch > 1 ? s0 : -1, nch);
+                if (is_split && m0 < split_max) split[m0] = make_int4(J, s0, nch, 0);
                 for (int ci = 0; ci < nch && w0 + ci < w_max; ++ci)
                     sched[w0 + ci] = make_int4(J, c0 + (ci * cnt) / nch, c0 + ((ci + 1) * cnt) / nch,
                                                nch > 1 ? s0 + ci : -1);
             }
             run_w += __shfl(w_incl, 63);
             run_s += __shfl(s_incl, 63);
+            run_m += __shfl(m_incl, 63);
         }
     }
     for (int w = run_w + lane; w < w_max; w += 64) sched[w] = make_int4(-1, 0, 0, -1);
+    for (int m = run_m + lane; m < split_max; m += 64) split[m] = make_int4(-1, 0, 0, 0);
 }
-
 
 }  // namespace spion
 #endif

@@ -123,10 +123,11 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ O,
     const T* __restrict__ dO, const float* __restrict__ LSE, T* __restrict__ dQ,
     float* __restrict__ delta_out, const int* __restrict__ row_ptr, const int* __restrict__ col_idx,
-    const int* __restrict__ col_ptr, int w_max, int4* __restrict__ sched, int2* __restrict__ colinfo,
+    const int* __restrict__ col_ptr, int w_max, int split_max, int4* __restrict__ sched,
+    int4* __restrict__ split,
     int L, int nb, float scale, float scale_log2) {
     if (blockIdx.x == 0 && threadIdx.x < 64)
-        build_key_schedule(col_ptr, nb, w_max, sched, colinfo, threadIdx.x);
+        build_key_schedule(col_ptr, nb, w_max, split_max, sched, split, threadIdx.x);
     typedef typename Elem<T>::Frag Frag;
     typedef typename Elem<T>::Quad Quad;
     constexpr int EPL = Elem<T>::EPL, KC = Elem<T>::KC, NDC = kD / KC, NKT = BS / 16;
@@ -288,25 +289,26 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_kernel(
 }
 
 // Adds the partial tiles of every block column that was cut into several chunks, in chunk order.
-// One thread per float4 of the bs x 64 output tile: workgroup = (head, block column J, part), 256
-// threads, bs / 16 parts per tile.
+// workgroup = (head, m-th split column, part): 256 threads, one float4 of the output tile each,
+// bs / 16 parts per tile, so that the loads of all chunks of a float4 are in flight together.
 template <typename T, int BS>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_reduce_kernel(
-    const float* __restrict__ partial, const int2* __restrict__ colinfo, int n_slots, T* __restrict__ dK,
-    T* __restrict__ dV, int L, int nb, float scale) {
+    const float* __restrict__ partial, const int4* __restrict__ split, int split_max, int n_slots,
+    T* __restrict__ dK, T* __restrict__ dV, int L, float scale) {
     constexpr int PARTS = BS / 16;
-    const int part = blockIdx.x % PARTS, J = (blockIdx.x / PARTS) % nb, bh = blockIdx.x / (PARTS * nb);
-    const int2 info = colinfo[J];
-    if (info.y <= 1) return;
+    const int part = blockIdx.x % PARTS, m = (blockIdx.x / PARTS) % split_max;
+    const int bh = blockIdx.x / (PARTS * split_max);
+    const int4 info = split[m];   // {J, first slot, chunks}
+    if (info.x < 0) return;
     const int v = part * 256 + threadIdx.x;
-    const float* pk = partial + ((size_t)bh * n_slots + info.x) * (2 * BS * kD) + v * 4;
+    const float* pk = partial + ((size_t)bh * n_slots + info.y) * (2 * BS * kD) + v * 4;
     f32x4 ak = f32x4{0.f, 0.f, 0.f, 0.f}, av = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int c = 0; c < info.y; ++c) {
+#pragma unroll 8
+    for (int c = 0; c < info.z; ++c) {
         ak += *reinterpret_cast<const f32x4*>(pk + (size_t)c * (2 * BS * kD));
         av += *reinterpret_cast<const f32x4*>(pk + (size_t)c * (2 * BS * kD) + BS * kD);
     }
-    const size_t out = (size_t)bh * L * kD + (size_t)J * BS * kD + v * 4;
+    const size_t out = (size_t)bh * L * kD + (size_t)info.x * BS * kD + v * 4;
     store_quad<T>(dK + out, ak * scale);
     store_quad<T>(dV + out, av);
 }
@@ -325,8 +327,9 @@ BwdWorkspace::BwdWorkspace(int BH, int L, int bs, int nb, int nnzb) {
     n_slots = key_slots_max(nnzb);
     delta_off = 0;
     sched_off = delta_off + up((size_t)BH * L * sizeof(float));
-    colinfo_off = sched_off + up((size_t)w_max * sizeof(int4));
-    partial_off = colinfo_off + up((size_t)nb * sizeof(int2));
+    split_max = key_split_max(nnzb);
+    split_off = sched_off + up((size_t)w_max * sizeof(int4));
+    partial_off = split_off + up((size_t)split_max * sizeof(int4));
     total = partial_off + up((size_t)BH * n_slots * 2 * bs * kD * sizeof(float));
 }
 
@@ -349,21 +352,22 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
     char* base = static_cast<char*>(workspace);
     float* delta = reinterpret_cast<float*>(base + ws.delta_off);
     int4* sched = reinterpret_cast<int4*>(base + ws.sched_off);
-    int2* colinfo = reinterpret_cast<int2*>(base + ws.colinfo_off);
+    int4* split = reinterpret_cast<int4*>(base + ws.split_off);
     float* partial = reinterpret_cast<float*>(base + ws.partial_off);
     const dim3 block(BS * 4);
     constexpr bool kTuned = sizeof(T) == 2 && BS >= 32;
     if constexpr (kTuned) {
         if (s.bwd_phases & 1) {
             const hipError_t e = bwd_dq_bf16<BS>(s, Q, K, V, O, dO, LSE, dQ, delta, row_ptr, col_idx, col_ptr,
-                                                 ws.w_max, sched, colinfo, st);
+                                                 ws.w_max, ws.split_max, sched, split, st);
             if (e != hipSuccess) return e;
         }
     } else if (s.bwd_phases & 1) {
         attn_bwd_dq_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
             static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
             static_cast<const T*>(O), static_cast<const T*>(dO), LSE, static_cast<T*>(dQ), delta,
-            row_ptr, col_idx, col_ptr, ws.w_max, sched, colinfo, s.L, s.nb, s.scale, s.scale * kLog2e);
+            row_ptr, col_idx, col_ptr, ws.w_max, ws.split_max, sched, split, s.L, s.nb, s.scale,
+            s.scale * kLog2e);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -380,8 +384,8 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         }
-        attn_bwd_dkv_reduce_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH * (BS / 16))), dim3(256), 0, st>>>(
-            partial, colinfo, ws.n_slots, static_cast<T*>(dK), static_cast<T*>(dV), s.L, s.nb, s.scale);
+        attn_bwd_dkv_reduce_kernel<T, BS><<<dim3((unsigned)(ws.split_max * s.BH * (BS / 16))), dim3(256), 0, st>>>(
+            partial, split, ws.split_max, ws.n_slots, static_cast<T*>(dK), static_cast<T*>(dV), s.L, s.scale);
     }
     return hipGetLastError();
 }

@@ -33,8 +33,8 @@ hipError_t launch_attn_bwd(const AttnShape& s, const void* Q, const void* K, con
 // Carving of the backward workspace: delta = rowsum(dO .* O) per query, the key-side work list, and
 // fp32 partial dK / dV tiles for block columns that are cut into several chunks.
 struct BwdWorkspace {
-    int w_max, n_slots;
-    size_t delta_off, sched_off, colinfo_off, partial_off, total;
+    int w_max, n_slots, split_max;
+    size_t delta_off, sched_off, split_off, partial_off, total;
     BwdWorkspace(int BH, int L, int bs, int nb, int nnzb);
 };
 size_t attn_bwd_workspace_bytes(int BH, int L, int bs, int nb, int nnzb);
@@ -46,8 +46,8 @@ hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void
 template <int BS>
 hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
                        const void* dO, const float* LSE, void* dQ, float* delta, const int* row_ptr,
-                       const int* col_idx, const int* col_ptr, int w_max, int4* sched, int2* colinfo,
-                       hipStream_t st);
+                       const int* col_idx, const int* col_ptr, int w_max, int split_max, int4* sched,
+                       int4* split, hipStream_t st);
 template <int BS>
 hipError_t bwd_dkv_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* dO,
                         const float* LSE, const float* delta, void* dK, void* dV, const int* row_idx,
