@@ -142,6 +142,26 @@ int spion_attn_bwd(const void *Q, const void *K, const void *V, const void *O, c
                    const int32_t *bsr_pos, int32_t nnzb, const spion_attn_params *p,
                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Producers of the pattern input.
+ *
+ * spion_score_mean: the score maps of the heads (and batch items) of a layer are averaged into the
+ * one map that pattern generation works on (Section 3: the heads of a layer show similar patterns).
+ *   A_maps  [n_maps, L, L] contiguous, dtype SPION_F32 or SPION_BF16;  A_s output [L, L] fp32:
+ *   A_s[i] = (A_maps[0][i] + A_maps[1][i] + ... in that order, fp32) * (1 / n_maps).  L % 8 == 0.
+ *
+ * spion_frobenius_distance: Eq. 2, distance = | ||A_prev||_F - ||A_cur||_F |, the quantity whose
+ * stagnation ends the dense-attention phase (Section 4.1).  fp64 accumulation, fixed summation order.
+ *   A_prev, A_cur  fp32 arrays of n elements (16-byte aligned);
+ *   out            device double[3]: {distance, ||A_prev||_F, ||A_cur||_F};
+ *   workspace      at least spion_frobenius_workspace_bytes() bytes, 256-byte aligned.
+ */
+int spion_score_mean(const void *A_maps, int32_t n_maps, int32_t L, int32_t dtype, float *A_s,
+                     void *hip_stream);
+size_t spion_frobenius_workspace_bytes(void);
+int spion_frobenius_distance(const float *A_prev, const float *A_cur, int64_t n, double *out,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of a spion_status value. */
 const char *spion_strerror(int status);
 

@@ -169,6 +169,29 @@ def generate_pattern(A: np.ndarray, bs: int, F: int, mode: int, value: float,
 
 
 # --------------------------------------------------------------------------------------------
+# producers of the pattern input
+# --------------------------------------------------------------------------------------------
+def score_mean(maps: np.ndarray) -> np.ndarray:
+    """maps: [n_maps, L, L]; element-wise mean in fp64."""
+    maps = np.ascontiguousarray(maps, dtype=np.float64)
+    n_maps = maps.shape[0]
+    out = np.empty(maps.shape[1:], dtype=np.float64)
+    _chk(lib().oracle_score_mean(_p(maps), ctypes.c_int32(n_maps), ctypes.c_int64(out.size), _p(out)),
+         "score_mean")
+    return out
+
+
+def frobenius_distance(a: np.ndarray, b: np.ndarray):
+    """Eq. 2; returns (distance, ||a||_F, ||b||_F) in fp64."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    b = np.ascontiguousarray(b, dtype=np.float64)
+    assert a.size == b.size
+    out = np.empty(3, dtype=np.float64)
+    _chk(lib().oracle_frobenius_distance(_p(a), _p(b), ctypes.c_int64(a.size), _p(out)), "frobenius_distance")
+    return float(out[0]), float(out[1]), float(out[2])
+
+
+# --------------------------------------------------------------------------------------------
 # attention
 # --------------------------------------------------------------------------------------------
 def _f64(x: np.ndarray) -> np.ndarray:

@@ -12,7 +12,9 @@
  *     kept here at block granularity: BSR and its transpose BSC);
  *   - attention: Eq. 1 (dense attention), Eq. 5 and Algorithm 5 lines 4-7 (SDDMM, sparse softmax,
  *     SpMM), Algorithm 6 (SparseSoftmax; its extra denominator term is available as a flag);
- *     the backward pass is the textbook gradient of Eq. 5 (the paper only states it exists).
+ *     the backward pass is the textbook gradient of Eq. 5 (the paper only states it exists);
+ *   - producers of the pattern input: the mean of the heads' score maps (Section 3) and the
+ *     Frobenius distance of Eq. 2.
  *
  * Arithmetic: attention in fp64.  Pattern in exact integers: every score is first quantised to
  * fixed point, a_q = rint(a * 2^40), so the sums of Eq. 3 and Eq. 4 are exact and independent of
@@ -274,6 +276,35 @@ int oracle_compact(const uint8_t *fl_out, int32_t nb, int32_t *row_ptr, int32_t 
         }
         col_ptr[nb] = m;
     }
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Producers of the pattern input
+ * ------------------------------------------------------------------------------------------- */
+
+/* Section 3: the score maps of the heads of a layer are averaged (element-wise mean, fp64). */
+int oracle_score_mean(const double *maps, int32_t n_maps, int64_t n, double *out) {
+    if (!maps || !out || n_maps <= 0 || n <= 0) return ORACLE_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        double s = 0.0;
+        for (int32_t m = 0; m < n_maps; ++m) s += maps[(int64_t)m * n + i];
+        out[i] = s / (double)n_maps;
+    }
+    return ORACLE_OK;
+}
+
+/* Eq. 2: distance = | sqrt(sum a^2) - sqrt(sum b^2) |; out = {distance, ||a||_F, ||b||_F}. */
+int oracle_frobenius_distance(const double *a, const double *b, int64_t n, double *out) {
+    if (!a || !b || !out || n <= 0) return ORACLE_ERR_ARG;
+    double sa = 0.0, sb = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        sa += a[i] * a[i];
+        sb += b[i] * b[i];
+    }
+    out[1] = sqrt(sa);
+    out[2] = sqrt(sb);
+    out[0] = fabs(out[1] - out[2]);
     return ORACLE_OK;
 }
 

@@ -11,4 +11,6 @@ from .binding import (  # noqa: F401
     lib_path, load, spion_version, spion_strerror,
     spion_pattern_workspace_bytes, spion_pattern, spion_attn_workspace_bytes,
     spion_attn_fwd, spion_attn_bwd, generate_pattern, attn_fwd, attn_bwd,
+    spion_score_mean, spion_frobenius_workspace_bytes, spion_frobenius_distance, score_mean,
+    frobenius_distance,
 )

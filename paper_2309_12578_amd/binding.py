@@ -66,6 +66,12 @@ def load() -> ctypes.CDLL:
     lib.spion_pattern_workspace_bytes.argtypes = [i32, i32]
     lib.spion_pattern.restype = ctypes.c_int
     lib.spion_pattern.argtypes = [vp, ctypes.POINTER(_PatternParams)] + [vp] * 8 + [vp, sz, vp]
+    lib.spion_score_mean.restype = ctypes.c_int
+    lib.spion_score_mean.argtypes = [vp, i32, i32, i32, vp, vp]
+    lib.spion_frobenius_workspace_bytes.restype = sz
+    lib.spion_frobenius_workspace_bytes.argtypes = []
+    lib.spion_frobenius_distance.restype = ctypes.c_int
+    lib.spion_frobenius_distance.argtypes = [vp, vp, ctypes.c_int64, vp, vp, sz, vp]
     lib.spion_attn_workspace_bytes.restype = sz
     lib.spion_attn_workspace_bytes.argtypes = [ctypes.POINTER(_AttnParams), i32, i32]
     lib.spion_attn_fwd.restype = ctypes.c_int
@@ -122,6 +128,24 @@ def spion_pattern(A_s, L, block, filt, thresh_mode, thresh_value, fl_out, row_pt
                               _ptr(workspace), ws_bytes, _stream(stream))
     if rc != 0:
         raise SpionError(rc, "spion_pattern")
+
+
+def spion_score_mean(A_maps, n_maps: int, L: int, dtype: int, A_s, stream=None) -> None:
+    rc = load().spion_score_mean(_ptr(A_maps), int(n_maps), int(L), int(dtype), _ptr(A_s), _stream(stream))
+    if rc != 0:
+        raise SpionError(rc, "spion_score_mean")
+
+
+def spion_frobenius_workspace_bytes() -> int:
+    return int(load().spion_frobenius_workspace_bytes())
+
+
+def spion_frobenius_distance(A_prev, A_cur, n: int, out, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().spion_frobenius_distance(_ptr(A_prev), _ptr(A_cur), int(n), _ptr(out), _ptr(workspace),
+                                         ws_bytes, _stream(stream))
+    if rc != 0:
+        raise SpionError(rc, "spion_frobenius_distance")
 
 
 def _attn_params(B, H, L, d, block, dtype, scale, flags) -> _AttnParams:
@@ -202,6 +226,26 @@ def generate_pattern(A_s: torch.Tensor, block: int, filt: int, thresh_mode: int,
                   flags=flags)
     if sync:
         out.nnzb = int(out.nnzb_dev.item())
+    return out
+
+
+def score_mean(A_maps: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """A_maps [n_maps, L, L] (fp32 or bf16) -> fp32 [L, L] mean map."""
+    n_maps, L, _ = A_maps.shape
+    if out is None:
+        out = torch.empty((L, L), dtype=torch.float32, device=A_maps.device)
+    spion_score_mean(A_maps, n_maps, L, _dtype_code(A_maps.dtype), out)
+    return out
+
+
+def frobenius_distance(A_prev: torch.Tensor, A_cur: torch.Tensor, out: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 2 on two fp32 maps; returns a device tensor {distance, ||A_prev||_F, ||A_cur||_F} (fp64)."""
+    if out is None:
+        out = torch.empty(3, dtype=torch.float64, device=A_prev.device)
+    if workspace is None:
+        workspace = torch.empty(spion_frobenius_workspace_bytes(), dtype=torch.uint8, device=A_prev.device)
+    spion_frobenius_distance(A_prev, A_cur, A_prev.numel(), out, workspace)
     return out
 
 

@@ -19,6 +19,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-
 SOURCES = [
     ("spion_api.hip", ["-ffp-contract=off"]),
     ("pattern_kernels.hip", ["-ffp-contract=off"]),
+    ("producer_kernels.hip", []),
     # MFMA accumulators in ordinary VGPRs: the softmax between two products reads them with VALU
     # instructions, and the AGPR form costs a register copy per value per step
     ("attn_kernels.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),

@@ -142,6 +142,33 @@ int spion_pattern(const float* A_s, const spion_pattern_params* p, uint8_t* fl_o
     return SPION_OK;
 }
 
+int spion_score_mean(const void* A_maps, int32_t n_maps, int32_t L, int32_t dtype, float* A_s,
+                     void* hip_stream) {
+    if (!A_maps || !A_s) return SPION_ERR_NULL;
+    if (dtype != SPION_F32 && dtype != SPION_BF16) return SPION_ERR_DTYPE;
+    if (n_maps <= 0 || L <= 0 || (L % 8) != 0) return SPION_ERR_SHAPE;
+    if (spion::launch_score_mean(A_maps, dtype == SPION_BF16, n_maps, (size_t)L * L, A_s,
+                                 static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return SPION_ERR_HIP;
+    return SPION_OK;
+}
+
+size_t spion_frobenius_workspace_bytes(void) { return align_up(spion::frobenius_workspace_bytes()); }
+
+int spion_frobenius_distance(const float* A_prev, const float* A_cur, int64_t n, double* out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!A_prev || !A_cur || !out) return SPION_ERR_NULL;
+    if (n <= 0) return SPION_ERR_SHAPE;
+    if (((uintptr_t)A_prev % 16) != 0 || ((uintptr_t)A_cur % 16) != 0) return SPION_ERR_PARAM;
+    if (!workspace || ((uintptr_t)workspace % kAlign) != 0 ||
+        workspace_bytes < spion_frobenius_workspace_bytes())
+        return SPION_ERR_WORKSPACE;
+    if (spion::launch_frobenius_distance(A_prev, A_cur, (size_t)n, out, workspace,
+                                         static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return SPION_ERR_HIP;
+    return SPION_OK;
+}
+
 size_t spion_attn_workspace_bytes(const spion_attn_params* p, int32_t nnzb, int32_t is_bwd) {
     if (!p || attn_params_ok(p, nnzb) != SPION_OK) return (size_t)-1;
     if (!is_bwd) return 0;

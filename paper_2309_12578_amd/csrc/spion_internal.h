@@ -14,6 +14,12 @@ hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long l
                                  uint8_t* fl, int* row_ptr, int* col_idx, int* col_ptr, int* row_idx,
                                  int* bsr_pos, int* nnzb, hipStream_t st);
 
+// producer_kernels.hip
+hipError_t launch_score_mean(const void* A, int is_bf16, int n_maps, size_t n, float* out, hipStream_t st);
+size_t frobenius_workspace_bytes();
+hipError_t launch_frobenius_distance(const float* a, const float* b, size_t n, double* out, void* workspace,
+                                     hipStream_t st);
+
 // attn_kernels.hip
 struct AttnShape {
     int BH, L, bs, nb;

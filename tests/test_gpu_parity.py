@@ -85,6 +85,17 @@ def test_pattern_bit_exact_on_random_maps_with_ties(sp, L, block, filt, mode, va
     _check_pattern(sp, A, block, filt, mode, value)
 
 
+def test_pattern_large_block_grid_uses_the_workspace_path(sp):
+    # nb = 256: the cell arrays no longer fit in LDS and live in the caller's workspace
+    L, block = 4096, 16
+    rng = np.random.default_rng(17)
+    A = (rng.random((L, L), dtype=np.float32) ** 8).astype(np.float32)
+    A[:, 1000:1016] += 0.5
+    A = np.minimum(A, 1.0).astype(np.float32)
+    _check_pattern(sp, A, block, 3, si.T_QUANTILE, 0.97)
+    _check_pattern(sp, A, block, 1, si.T_MEAN_KSTD, 2.0)
+
+
 def test_pattern_plateau_map_and_tiny_values(sp):
     L, block = 128, 16
     A = np.zeros((L, L), dtype=np.float32)        # every pooled value equal: all ties
@@ -112,6 +123,50 @@ def test_pattern_is_deterministic_across_runs(sp):
         again = sp.generate_pattern(A, w.block, w.filt, w.thresh_mode, w.thresh_value)
         assert torch.equal(first.fl_out, again.fl_out) and torch.equal(first.pool_sum, again.pool_sum)
         assert torch.equal(first.col_idx[:first.nnzb], again.col_idx[:again.nnzb])
+
+
+# ------------------------------------------------------------------------------------------------
+# producers of the pattern input
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_maps,L", [(1, 64), (7, 264), (16, 1024)])
+def test_score_mean_matches_oracle(sp, dtype, n_maps, L):
+    rng = np.random.default_rng(n_maps * 1000 + L)
+    maps = si.round_to_dtype(rng.random((n_maps, L, L), dtype=np.float32) ** 4, dtype)
+    got = sp.score_mean(_dev(maps, _torch_dtype(dtype))).cpu().numpy().astype(np.float64)
+    ref = oracle.score_mean(maps)
+    # fp32 sequential sum of n_maps terms, then one division
+    assert np.all(np.abs(got - ref) <= 1e-6 * np.abs(ref) + 1e-12), np.abs(got - ref).max()
+
+
+@pytest.mark.parametrize("n", [16, 1000, 4099, 1024 * 1024, 4096 * 4096])
+def test_frobenius_distance_matches_oracle(sp, n):
+    rng = np.random.default_rng(n)
+    a = rng.random(n, dtype=np.float32)
+    b = (rng.random(n, dtype=np.float32) * 1.01).astype(np.float32)
+    out = sp.frobenius_distance(_dev(a), _dev(b)).cpu().numpy()
+    d, na, nb_ = oracle.frobenius_distance(a, b)
+    assert out[1] == pytest.approx(na, rel=1e-12) and out[2] == pytest.approx(nb_, rel=1e-12)
+    assert out[0] == pytest.approx(d, rel=1e-9, abs=1e-12 * na)
+    again = sp.frobenius_distance(_dev(a), _dev(b)).cpu().numpy()
+    assert np.array_equal(out, again)                     # fixed summation order
+
+
+def test_pattern_from_gpu_averaged_map(sp):
+    # the whole producer + pattern chain on device: per-head maps -> mean -> spion_pattern
+    w = si.workload(1)
+    rng = np.random.default_rng(5)
+    heads = []
+    Q, K, _, _ = si.make_qkv_do(w)
+    base = si.make_score_map(w, Q, K)
+    for h in range(6):
+        heads.append((base * (0.5 + rng.random(base.shape, dtype=np.float32))).astype(np.float32))
+    maps = np.minimum(np.stack(heads), 1.0).astype(np.float32)
+    A_dev = sp.score_mean(_dev(maps))
+    A = A_dev.cpu().numpy()
+    pat = sp.generate_pattern(A_dev, w.block, w.filt, w.thresh_mode, w.thresh_value)
+    ref = oracle.generate_pattern(A, w.block, w.filt, w.thresh_mode, w.thresh_value)
+    assert np.array_equal(pat.fl_out.cpu().numpy(), ref["fl_out"])
 
 
 # ------------------------------------------------------------------------------------------------

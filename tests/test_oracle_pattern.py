@@ -339,3 +339,32 @@ def test_generate_pattern_finds_planted_band_on_tiny_workload():
         conv[lo:hi, lo:hi] += A[lo + f:hi + f, lo + f:hi + f].astype(np.float64)
     ref = conv.reshape(w.nb, w.block, w.nb, w.block).sum(axis=(1, 3))
     assert np.allclose(out["pool_sum"] / ONE, ref, rtol=0, atol=w.block ** 2 * w.filt * 2.0 ** -40)
+
+
+# ------------------------------------------------------------------ producers of the pattern input
+def test_score_mean_matches_numpy_and_special_cases():
+    rng = np.random.default_rng(21)
+    maps = rng.random((5, 12, 12))
+    assert np.allclose(oracle.score_mean(maps), maps.mean(axis=0), rtol=1e-15)
+    assert np.array_equal(oracle.score_mean(maps[:1]), maps[0])            # one map: identity
+    const = np.stack([np.full((4, 4), v) for v in (1.0, 2.0, 6.0)])
+    assert np.array_equal(oracle.score_mean(const), np.full((4, 4), 3.0))
+    # the mean is taken over maps, not over rows or columns
+    two = np.zeros((2, 2, 2))
+    two[0, 0, 1] = 4.0
+    assert oracle.score_mean(two).tolist() == [[0.0, 2.0], [0.0, 0.0]]
+
+
+def test_frobenius_distance_hand_case_and_numpy():
+    a = np.array([[3.0, 0.0], [0.0, 4.0]])        # norm 5
+    b = np.array([[5.0, 12.0], [0.0, 0.0]])       # norm 13
+    d, na, nb_ = oracle.frobenius_distance(a, b)
+    assert (d, na, nb_) == (8.0, 5.0, 13.0)
+    assert oracle.frobenius_distance(b, a)[0] == 8.0                      # absolute value
+    rng = np.random.default_rng(22)
+    x, y = rng.standard_normal((2, 50, 50))
+    d, nx, ny = oracle.frobenius_distance(x, y)
+    assert nx == pytest.approx(np.linalg.norm(x), rel=1e-14) and ny == pytest.approx(np.linalg.norm(y), rel=1e-14)
+    assert d == pytest.approx(abs(np.linalg.norm(x) - np.linalg.norm(y)), rel=1e-10)
+    # Eq. 2 is the difference of the norms, not the norm of the difference
+    assert oracle.frobenius_distance(a, -a)[0] == 0.0
