@@ -14,3 +14,4 @@ from .binding import (  # noqa: F401
     spion_score_mean, spion_frobenius_workspace_bytes, spion_frobenius_distance, score_mean,
     frobenius_distance,
 )
+from .autograd import sparse_attention  # noqa: E402,F401

@@ -312,6 +312,29 @@ def test_attention_workloads_full_size(sp, name, heads):
     print(name, f"nnzb={pat.nnzb}", {k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in errs.items()})
 
 
+def test_autograd_wrapper_matches_torch_masked_attention(sp):
+    # the autograd front end against plain fp32 torch ops on the GPU (dense masked attention)
+    block, nb, B, H, d = 32, 6, 2, 2, 64
+    L = nb * block
+    torch.manual_seed(0)
+    fl = si.random_block_mask(nb, 0.4, seed=4)
+    pat = _pattern_from_mask(sp, fl, block)
+    q, k, v = [torch.randn(B, H, L, d, device="cuda", requires_grad=True) for _ in range(3)]
+    do = torch.randn(B, H, L, d, device="cuda")
+    o = sp.sparse_attention(q, k, v, pat)
+    o.backward(do)
+    got = [o.detach(), q.grad.clone(), k.grad.clone(), v.grad.clone()]
+    for t in (q, k, v):
+        t.grad = None
+    P = torch.from_numpy(oracle.upsample(fl, block)).cuda().bool()
+    s = (q @ k.transpose(-1, -2)) / 8.0
+    ref = torch.softmax(s.masked_fill(~P, float("-inf")), dim=-1) @ v
+    ref.backward(do)
+    for g, r in zip(got, [ref.detach(), q.grad, k.grad, v.grad]):
+        err = (g - r).norm() / r.norm()
+        assert err < 5e-5, float(err)     # torch's own fp32 matmuls are the looser side here
+
+
 def test_attention_backward_is_deterministic(sp):
     w = si.workload(2)
     Q, K, V, dO = si.make_qkv_do(w, bh_limit=8)
