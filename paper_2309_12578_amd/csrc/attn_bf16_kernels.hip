@@ -469,13 +469,507 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
+// Tiles loaded by the memory pipeline straight into LDS (global_load_lds, 16 B per lane; a wave
+// instruction fills 1 KB of consecutive LDS, lane l at byte 16 l).  Rows are 128 B apart with no
+// padding, so the 16-byte slots of a row are permuted instead: slot s of row `row` holds the row's
+// chunk s ^ swz(row), swz = 2 * ((row >> 1) & 3).  Measured with SQ_LDS_BANK_CONFLICT: neither the
+// 16-byte fragment reads (lane = row) nor the transpose reads (8 rows x 32 B per half wave) conflict
+// in this layout.  (A 16-byte read is served 16 lanes at a time, lanes 0-7 together with lanes of the
+// upper half of a neighbouring group of 16: a permutation that also used bit 3 of the row conflicted.)
+// ------------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8]); the
+// counters not named are left at their maximum, i.e. not waited for
+constexpr int kWaitVm0 = 0x0F70, kWaitVm4 = 0x0F74, kWaitVm5 = 0x0F75, kWaitLgkm0 = 0xC07F;
+
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) << 1; }
+
+// A workgroup of BS / 16 waves loads a BS x 64 tile with two instructions per wave.  `src` and
+// `wave` are wave-uniform (the wave index comes from readfirstlane), so each load is a scalar base
+// plus the lane's fixed 32-bit offset TileLoadLane::off[k].
+struct TileLoadLane {
+    unsigned off[2];   // byte offset of this lane's 16 bytes within the tile, for piece 2 wave + k
+    __device__ __forceinline__ TileLoadLane(int wave, int lane) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int chunk = (lane & 7) ^ (((lane >> 4) & 3) << 1);   // swz(8 piece + lane / 8)
+            off[k] = (unsigned)(((2 * wave + k) * 8 + (lane >> 3)) * kD + chunk * 8) * (unsigned)sizeof(bf16_t);
+        }
+    }
+};
+__device__ __forceinline__ void tile_load_async(const bf16_t* __restrict__ src, bf16_t* tile, int wave,
+                                                const TileLoadLane& tl) {
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+        __builtin_amdgcn_global_load_lds(reinterpret_cast<const char*>(src) + tl.off[k],
+                                         (lds_void_ptr)(tile + (2 * wave + k) * 512), 16, 0, 0);
+}
+
+// Per-lane read offsets into such a tile (in elements), fixed for the whole kernel.
+struct SwzLane {
+    int frag[2];   // 16-byte fragment of row r, chunk 4 c + g; add 1024 per 16-row tile
+    int tr_row;    // transpose read: row 4 g + r / 4, element offset 4 (r & 1) within the slot
+    int tr_sw;     // swz of that row
+    int tr_b;      // (r >> 1) & 1: which slot of the 32-byte pair
+    __device__ __forceinline__ SwzLane(int r, int g) {
+        const int sw = swz(r);
+        frag[0] = r * kD + ((g ^ sw) << 3);
+        frag[1] = r * kD + (((4 + g) ^ sw) << 3);
+        const int trow = 4 * g + (r >> 2);
+        tr_row = trow * kD + 4 * (r & 1);
+        tr_sw = swz(trow);
+        tr_b = (r >> 1) & 1;
+    }
+    __device__ __forceinline__ int tr(int dt) const { return tr_row + ((((dt << 1) | tr_b) ^ tr_sw) << 3); }
+};
+
+// acc[dt][i] (d = 16 dt + 4 g + i, owned row r) += sum over the tile's rows of
+// tile[row][16 dt + ...] * x[row][r], the tile in the permuted-slot layout.
+template <int BS>
+__device__ __forceinline__ void mma_over_rows_swz(f32x4 (&acc)[4], const bf16_t* tile,
+                                                  const bf16x4 (&x)[BS / 16], const SwzLane& sl) {
+#pragma unroll
+    for (int pc = 0; pc < BS / 32; ++pc) {
+        const bf16x8 xf = join(x[2 * pc], x[2 * pc + 1]);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            const int o = sl.tr(dt) + pc * 32 * kD;
+            acc[dt] = mma_d(acc[dt], join(lds_read_tr(tile + o), lds_read_tr(tile + 16 * kD + o)), xf);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, key side, loads through the memory pipeline: Q, dO, LSE and delta of block it + 2 are
+// loaded straight into the third LDS stage while block it is multiplied: one barrier per block, no
+// staging registers, no LDS stores.
+// ------------------------------------------------------------------------------------------------
+template <int BS>
+struct DkvSmem {
+    bf16_t q[BS * kD];
+    bf16_t d[BS * kD];
+    float lse[BS];
+    float del[BS];
+};
+
+template <int BS>
+__global__ __launch_bounds__(BS * 4) void attn_bwd_dkv2_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, const int* __restrict__ row_idx,
+    const int4* __restrict__ sched, int w_max, int total, int n_slots, float* __restrict__ partial, int L,
+    float scale, float scale_log2) {
+    constexpr int NQT = BS / 16;
+    // separate objects, so that the compiler can tell a read of one stage from a load in flight into
+    // another and does not wait for it
+    __shared__ __attribute__((aligned(16))) DkvSmem<BS> sm0, sm1, sm2;
+
+    const int vid = xcd_remap(blockIdx.x, total);
+    const int w = vid % w_max, bh = vid / w_max;
+    const int4 item = sched[w];
+    const int J = item.x, n = item.z - item.y, slot = item.w;
+    if (J < 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const size_t head = (size_t)bh * L * kD;
+    const size_t vec = (size_t)bh * L;
+    const int krow = J * BS + wave * 16 + r;
+    const int last = n > 0 ? n - 1 : 0;
+    const int* rows = row_idx + item.y;
+    const SwzLane sl(r, g);
+    const TileLoadLane tl(wave, lane);
+
+    // a group of 4 tile loads per wave, plus one 4-byte-per-lane load in waves 0 (LSE) and 1 (delta)
+    auto issue = [&](DkvSmem<BS>& st, int I) {
+        tile_load_async(Q + head + (size_t)I * BS * kD, st.q, wave, tl);
+        tile_load_async(dO + head + (size_t)I * BS * kD, st.d, wave, tl);
+        if (wave == 0) {
+            if (lane < BS)
+                __builtin_amdgcn_global_load_lds(LSE + vec + (size_t)I * BS + lane, (lds_void_ptr)st.lse, 4, 0, 0);
+        } else if (wave == 1) {
+            if (lane < BS)
+                __builtin_amdgcn_global_load_lds(delta + vec + (size_t)I * BS + lane, (lds_void_ptr)st.del, 4, 0, 0);
+        }
+    };
+
+    int Ipre = n > 0 ? rows[2 < last ? 2 : last] : 0;   // block of step it + 2
+    if (n > 0) issue(sm0, rows[0]);
+    if (n > 1) issue(sm1, rows[1]);
+    // owned K / V fragments (step 0 waits for everything issued up to here)
+    bf16x8 kf[2], vf[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const size_t off = head + (size_t)krow * kD + c * 32 + g * 8;
+        kf[c] = *reinterpret_cast<const bf16x8*>(K + off);
+        vf[c] = *reinterpret_cast<const bf16x8*>(V + off);
+    }
+
+    f32x4 dk[4], dv[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        dk[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        dv[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    auto step = [&](const DkvSmem<BS>& cur, DkvSmem<BS>& nxt2, int it) {
+        // wait until this wave's part of block `it` has landed; the group of block it + 1 may fly on
+        if (it + 1 < n && it > 0) {
+            if (wave < 2) __builtin_amdgcn_s_waitcnt(kWaitVm5);
+            else __builtin_amdgcn_s_waitcnt(kWaitVm4);
+        } else {
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);   // step 0 also waits for the owned K / V fragments
+        }
+        // everyone's part has landed and the stage of block it - 1 is no longer read.  A bare barrier:
+        // the fences of __syncthreads would wait for every load in flight, the next block's included
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (it + 2 < n) issue(nxt2, Ipre);
+        Ipre = rows[it + 3 < last ? it + 3 : last];
+        bf16x4 pq[NQT], dsq[NQT];
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) {
+            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, dp = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                s = mma_d(s, *reinterpret_cast<const bf16x8*>(cur.q + qt * 16 * kD + sl.frag[c]), kf[c]);    // S = Q K^T
+                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(cur.d + qt * 16 * kD + sl.frag[c]), vf[c]);  // dP = dO V^T
+            }
+            const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&cur.lse[qt * 16 + 4 * g]) * kLog2e;
+            const f32x4 del4 = *reinterpret_cast<const f32x4*>(&cur.del[qt * 16 + 4 * g]);
+            f32x4 p, ds;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                p[i] = fast_exp2(fmaf(s[i], scale_log2, -lse4[i]));
+                ds[i] = p[i] * (dp[i] - del4[i]);
+            }
+            pq[qt] = to_quad<bf16_t>(p);
+            dsq[qt] = to_quad<bf16_t>(ds);
+        }
+        mma_over_rows_swz<BS>(dv, cur.d, pq, sl);    // dV^T[d][key] += dO^T P
+        mma_over_rows_swz<BS>(dk, cur.q, dsq, sl);   // dK^T[d][key] += Q^T dS
+    };
+
+    for (int it = 0; it < n; it += 3) {
+        step(sm0, sm2, it);
+        if (it + 1 < n) step(sm1, sm0, it + 1);
+        if (it + 2 < n) step(sm2, sm1, it + 2);
+    }
+
+    if (slot < 0) {
+        bf16_t* dkrow = dK + head + (size_t)krow * kD;
+        bf16_t* dvrow = dV + head + (size_t)krow * kD;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            store_quad<bf16_t>(dkrow + dt * 16 + 4 * g, dk[dt] * scale);
+            store_quad<bf16_t>(dvrow + dt * 16 + 4 * g, dv[dt]);
+        }
+    } else {
+        // fp32 partial tile of this chunk, unscaled: [head][slot][dK | dV][bs][64]
+        float* pk = partial + ((size_t)bh * n_slots + slot) * (2 * BS * kD) + (size_t)(wave * 16 + r) * kD;
+        float* pv = pk + BS * kD;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            *reinterpret_cast<f32x4*>(pk + dt * 16 + 4 * g) = dk[dt];
+            *reinterpret_cast<f32x4*>(pv + dt * 16 + 4 * g) = dv[dt];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward and backward query side with K / V tiles loaded through the memory pipeline, NS stages
+// (prefetch distance NS - 1 blocks), one barrier per block
+// ------------------------------------------------------------------------------------------------
+template <int BS>
+struct KvSmem {
+    bf16_t k[BS * kD];
+    bf16_t v[BS * kD];
+};
+
+// Wait until this wave's loads of block `it` have landed (the younger groups, 4 loads each, may stay
+// in flight), then meet the other waves: their parts have landed too and nobody reads the stage of
+// block it - 1 any more.  A bare barrier: the fences of __syncthreads would wait for every load in
+// flight, the prefetched blocks included.
+template <int NS>
+__device__ __forceinline__ void stage_ready(int it, int n) {
+    if (NS == 3 && it > 0 && it + 1 < n) __builtin_amdgcn_s_waitcnt(kWaitVm4);
+    else __builtin_amdgcn_s_waitcnt(kWaitVm0);   // step 0 also waits for the owned-row fragments
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// Walk order of a block row.  The diagonal block (I, I) is kept by every pattern the generator makes,
+// and its address needs no index lookup, so the row-walking kernels start loading it before they
+// have read row_ptr / col_idx and visit it first; the other kept blocks follow in index order.  (The
+// order of the blocks changes the rounding of the sums only.)  pd = position of I among the row's
+// entries, or -1 if the row has no diagonal block: then the walk is in index order and the early
+// load is thrown away.
+__device__ __forceinline__ int find_in_row(const int* __restrict__ cols, int n, int I, int lane) {
+    for (int base = 0; base < n; base += 64) {
+        const int c = base + lane < n ? cols[base + lane] : -1;
+        const unsigned long long hit = __ballot(c == I);
+        if (hit) return base + __builtin_ctzll(hit);
+    }
+    return -1;
+}
+__device__ __forceinline__ int walk_index(int t, int pd) {
+    return pd < 0 ? t : (t == 0 ? pd : (t - 1 < pd ? t - 1 : t));
+}
+
+template <int BS, int NS>
+__global__ __launch_bounds__(BS * 4) void attn_fwd2_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    bf16_t* __restrict__ O, float* __restrict__ LSE, const int* __restrict__ row_ptr,
+    const int* __restrict__ col_idx, int L, int nb, int total, float scale_log2, int paper_denom) {
+    constexpr int NKT = BS / 16, D = NS - 1;
+    __shared__ __attribute__((aligned(16))) KvSmem<BS> sm0, sm1, sm2;   // sm2 unused (removed) for NS == 2
+
+    const int vid = xcd_remap(blockIdx.x, total);
+    const int I = vid % nb, bh = vid / nb;
+    const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const size_t head = (size_t)bh * L * kD;
+    const int qrow = I * BS + wave * 16 + r;
+    const SwzLane sl(r, g);
+    const TileLoadLane tl(wave, lane);
+
+    auto issue = [&](KvSmem<BS>& st, int J) {
+        tile_load_async(K + head + (size_t)J * BS * kD, st.k, wave, tl);
+        tile_load_async(V + head + (size_t)J * BS * kD, st.v, wave, tl);
+    };
+    issue(sm0, I);   // the diagonal block, before any index is known
+    const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
+    const int last = n > 0 ? n - 1 : 0;
+    const int* cols = col_idx + jb;
+    const int pd = __builtin_amdgcn_readfirstlane(find_in_row(cols, n, I, lane));
+    // block visited at step t (clamped reads stay inside this row's entries; an empty row reads nothing)
+    auto col_at = [&](int t) { return cols[walk_index(t < last ? t : last, pd)]; };
+    if (pd < 0 && n > 0) {
+        // no diagonal block in this row: once everyone's early load has landed, load block 0 over it
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue(sm0, cols[0]);
+    }
+    if (D > 1 && n > 1) issue(sm1, col_at(1));
+    int Jpre = n > 0 ? col_at(D) : 0;   // block of step it + D
+
+    bf16x8 qf[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+        qf[c] = *reinterpret_cast<const bf16x8*>(Q + head + (size_t)qrow * kD + c * 32 + g * 8);
+
+    float m = -INFINITY;   // running row maximum in log2 units (score * scale * log2 e)
+    f32x4 lacc = f32x4{0.f, 0.f, 0.f, 0.f};   // running row sum, replicated in its 4 elements
+    f32x4 oacc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)1.0f;
+
+    auto step = [&](const KvSmem<BS>& cur, KvSmem<BS>& tgt, int it) {
+        stage_ready<NS>(it, n);
+        if (it + D < n) issue(tgt, Jpre);
+        Jpre = col_at(it + D + 1);
+        // S^T tile kt: [key 16 kt + 4 g + i][query r]
+        f32x4 s[NKT];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+            s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                s[kt] = mma_d(s[kt], *reinterpret_cast<const bf16x8*>(cur.k + kt * 16 * kD + sl.frag[c]), qf[c]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[kt][i]);
+        }
+        mx = group_max(mx);
+        const float m_new = fmaxf(m, mx * scale_log2);
+        if (__any(m_new > m)) {   // some row's running maximum moved: rescale what is accumulated
+            const float alpha = fast_exp2(m - m_new);
+            lacc *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) oacc[dt] *= alpha;
+        }
+        bf16x4 pq[NKT];
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[kt][i] = fast_exp2(fmaf(s[kt][i], scale_log2, -m_new));
+            pq[kt] = to_quad<bf16_t>(s[kt]);
+        }
+        // row sums on the MFMA pipe: a tile of ones times P^T adds up each owned row's probabilities
+        // (the bf16 values that also enter P V), every accumulator element holding the same sum
+#pragma unroll
+        for (int pc = 0; pc < BS / 32; ++pc) lacc = mma_d(lacc, ones, join(pq[2 * pc], pq[2 * pc + 1]));
+        m = m_new;
+        mma_over_rows_swz<BS>(oacc, cur.v, pq, sl);   // O^T[d][query] += V^T P^T
+    };
+
+    if constexpr (NS == 3) {
+        for (int it = 0; it < n; it += 3) {
+            step(sm0, sm2, it);
+            if (it + 1 < n) step(sm1, sm0, it + 1);
+            if (it + 2 < n) step(sm2, sm1, it + 2);
+        }
+    } else {
+        for (int it = 0; it < n; it += 2) {
+            step(sm0, sm1, it);
+            if (it + 1 < n) step(sm1, sm0, it + 1);
+        }
+    }
+
+    // an empty row never waited for its early load: it must land before this workgroup's LDS is freed
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+
+    float lsum = lacc[0];
+    if (paper_denom) {
+        // Algorithm 6: every masked entry of the row counts as a score of 0
+        const float masked = (float)(L - n * BS);
+        const float mp = fmaxf(m, 0.f);
+        const float a = exp2f(m - mp);
+        lsum = lsum * a + masked * exp2f(-mp);
+        m = mp;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) oacc[dt] *= a;
+    }
+    const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+    bf16_t* orow = O + head + (size_t)qrow * kD;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) store_quad<bf16_t>(orow + dt * 16 + 4 * g, oacc[dt] * inv);
+    if (g == 0) LSE[(size_t)bh * L + qrow] = lsum > 0.f ? (m + log2f(lsum)) * kLn2 : -INFINITY;
+}
+
+template <int BS, int NS>
+__global__ __launch_bounds__(BS * 4) void attn_bwd_dq2_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, const float* __restrict__ LSE,
+    bf16_t* __restrict__ dQ, float* __restrict__ delta_out, const int* __restrict__ row_ptr,
+    const int* __restrict__ col_idx, const int* __restrict__ col_ptr, int w_max, int split_max,
+    int4* __restrict__ sched, int4* __restrict__ split, int L, int nb, int total, float scale,
+    float scale_log2) {
+    constexpr int NKT = BS / 16, D = NS - 1;
+    __shared__ __attribute__((aligned(16))) KvSmem<BS> sm0, sm1, sm2;
+
+    const int vid = xcd_remap(blockIdx.x, total);
+    const int I = vid % nb, bh = vid / nb;
+    const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const size_t head = (size_t)bh * L * kD;
+    const int qrow = I * BS + wave * 16 + r;
+    const SwzLane sl(r, g);
+    const TileLoadLane tl(wave, lane);
+
+    auto issue = [&](KvSmem<BS>& st, int J) {
+        tile_load_async(K + head + (size_t)J * BS * kD, st.k, wave, tl);
+        tile_load_async(V + head + (size_t)J * BS * kD, st.v, wave, tl);
+    };
+    issue(sm0, I);   // the diagonal block, before any index is known
+    const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
+    const int last = n > 0 ? n - 1 : 0;
+    const int* cols = col_idx + jb;
+    const int pd = __builtin_amdgcn_readfirstlane(find_in_row(cols, n, I, lane));
+    // block visited at step t (clamped reads stay inside this row's entries; an empty row reads nothing)
+    auto col_at = [&](int t) { return cols[walk_index(t < last ? t : last, pd)]; };
+    if (pd < 0 && n > 0) {
+        // no diagonal block in this row: once everyone's early load has landed, load block 0 over it
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue(sm0, cols[0]);
+    }
+    if (D > 1 && n > 1) issue(sm1, col_at(1));
+    int Jpre = n > 0 ? col_at(D) : 0;   // block of step it + D
+
+    if (vid == 0 && tid < 64) build_key_schedule(col_ptr, nb, w_max, split_max, sched, split, tid);
+
+    bf16x8 qf[2], dof[2];
+    float delta = 0.f;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const size_t off = head + (size_t)qrow * kD + c * 32 + g * 8;
+        qf[c] = *reinterpret_cast<const bf16x8*>(Q + off);
+        dof[c] = *reinterpret_cast<const bf16x8*>(dO + off);
+        const bf16x8 of = *reinterpret_cast<const bf16x8*>(O + off);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) delta = fmaf((float)dof[c][e], (float)of[e], delta);
+    }
+    delta = group_sum(delta);
+    if (g == 0) delta_out[(size_t)bh * L + qrow] = delta;
+    const float lse2 = LSE[(size_t)bh * L + qrow] * kLog2e;
+
+    f32x4 dq[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) dq[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto step = [&](const KvSmem<BS>& cur, KvSmem<BS>& tgt, int it) {
+        stage_ready<NS>(it, n);
+        if (it + D < n) issue(tgt, Jpre);
+        Jpre = col_at(it + D + 1);
+        bf16x4 dsq[NKT];
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, dp = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int off = kt * 16 * kD + sl.frag[c];
+                s = mma_d(s, *reinterpret_cast<const bf16x8*>(cur.k + off), qf[c]);      // S^T = K Q^T
+                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(cur.v + off), dof[c]);   // dP^T = V dO^T
+            }
+            f32x4 ds;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p = fast_exp2(fmaf(s[i], scale_log2, -lse2));
+                ds[i] = p * (dp[i] - delta);
+            }
+            dsq[kt] = to_quad<bf16_t>(ds);
+        }
+        mma_over_rows_swz<BS>(dq, cur.k, dsq, sl);    // dQ^T[d][query] += K^T dS^T
+    };
+
+    if constexpr (NS == 3) {
+        for (int it = 0; it < n; it += 3) {
+            step(sm0, sm2, it);
+            if (it + 1 < n) step(sm1, sm0, it + 1);
+            if (it + 2 < n) step(sm2, sm1, it + 2);
+        }
+    } else {
+        for (int it = 0; it < n; it += 2) {
+            step(sm0, sm1, it);
+            if (it + 1 < n) step(sm1, sm0, it + 1);
+        }
+    }
+    // an empty row never waited for its early load: it must land before this workgroup's LDS is freed
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    bf16_t* drow = dQ + head + (size_t)qrow * kD;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) store_quad<bf16_t>(drow + dt * 16 + 4 * g, dq[dt] * scale);
+}
+
+#ifndef SPION_FWD_NS
+#define SPION_FWD_NS 2
+#endif
+#ifndef SPION_DQ_NS
+#define SPION_DQ_NS 2
+#endif
+
+// ------------------------------------------------------------------------------------------------
 // launchers (called by the dispatch in attn_kernels.hip)
 // ------------------------------------------------------------------------------------------------
 template <int BS>
 hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, void* O, float* LSE,
                     const int* row_ptr, const int* col_idx, hipStream_t st) {
     const int total = s.nb * s.BH;
+#if SPION_FWD_NS > 0
+    attn_fwd2_bf16_kernel<BS, SPION_FWD_NS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+#else
     attn_fwd_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+#endif
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
         static_cast<bf16_t*>(O), LSE, row_ptr, col_idx, s.L, s.nb, total, s.scale * kLog2e, s.paper_denom);
     return hipGetLastError();
@@ -487,7 +981,11 @@ hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const v
                        const int* col_idx, const int* col_ptr, int w_max, int split_max, int4* sched,
                        int4* split, hipStream_t st) {
     const int total = s.nb * s.BH;
+#if SPION_DQ_NS > 0
+    attn_bwd_dq2_bf16_kernel<BS, SPION_DQ_NS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+#else
     attn_bwd_dq_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+#endif
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
         static_cast<const bf16_t*>(O), static_cast<const bf16_t*>(dO), LSE, static_cast<bf16_t*>(dQ), delta,
         row_ptr, col_idx, col_ptr, w_max, split_max, sched, split, s.L, s.nb, total, s.scale,
@@ -500,7 +998,11 @@ hipError_t bwd_dkv_bf16(const AttnShape& s, const void* Q, const void* K, const 
                         const float* LSE, const float* delta, void* dK, void* dV, const int* row_idx,
                         const int4* sched, int w_max, int n_slots, float* partial, hipStream_t st) {
     const int total = w_max * s.BH;
+#ifndef SPION_DKV_V1
+    attn_bwd_dkv2_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+#else
     attn_bwd_dkv_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+#endif
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
         static_cast<const bf16_t*>(dO), LSE, delta, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV),
         row_idx, sched, w_max, total, n_slots, partial, s.L, s.scale, s.scale * kLog2e);

@@ -256,6 +256,39 @@ def test_attention_degenerate_patterns(sp, dtype):
     _run_attention_case(sp, Q[:, :block], K[:, :block], V[:, :block], dO[:, :block], one, block, dtype)
 
 
+@pytest.mark.parametrize("block", [32, 64])
+def test_attention_rows_without_a_diagonal_block(sp, block):
+    # the bf16 row-walking kernels load the diagonal block early and visit it first; rows that do not
+    # keep it take another path, and so do rows whose diagonal entry lies beyond the first 64 entries
+    nb, BH, d = 6, 2, 64
+    L = nb * block
+    rng = np.random.default_rng(17 + block)
+    Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), "bf16")
+                   for _ in range(4)]
+    fl = si.random_block_mask(nb, 0.5, seed=block + 1)
+    fl[np.arange(nb), np.arange(nb)] = 0                     # no row keeps its diagonal block
+    fl[0, :] = 0
+    fl[0, nb - 1] = 1                                        # single off-diagonal block
+    fl[3, :] = 0                                             # empty row
+    _run_attention_case(sp, Q, K, V, dO, fl, block, "bf16")
+    anti = np.fliplr(np.eye(nb, dtype=np.uint8))             # anti-diagonal only
+    _run_attention_case(sp, Q, K, V, dO, anti, block, "bf16")
+
+
+def test_attention_long_rows_find_their_diagonal(sp):
+    block, nb, BH, d = 32, 72, 1, 64                         # rows with more than 64 kept blocks
+    L = nb * block
+    rng = np.random.default_rng(23)
+    Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), "bf16")
+                   for _ in range(4)]
+    fl = np.eye(nb, dtype=np.uint8)
+    fl[70, :] = 1                                            # diagonal entry at position 70
+    fl[68, :] = 1
+    fl[68, 68] = 0                                           # 71 entries, none of them the diagonal
+    fl[5, :] = 1                                             # diagonal entry at position 5
+    _run_attention_case(sp, Q, K, V, dO, fl, block, "bf16")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_tall_columns_are_split_into_chunks(sp, dtype):
     # columns with more kept rows than one key-side work item takes (8): 9, 17 and 20 rows
