@@ -15,3 +15,4 @@ from .binding import (  # noqa: F401
     frobenius_distance,
 )
 from .autograd import sparse_attention  # noqa: E402,F401
+from .sublayer import SparseMHA  # noqa: E402,F401

@@ -368,6 +368,41 @@ def test_autograd_wrapper_matches_torch_masked_attention(sp):
         assert err < 5e-5, float(err)     # torch's own fp32 matmuls are the looser side here
 
 
+@pytest.mark.parametrize("tdt", [torch.float32, torch.bfloat16])
+def test_sparse_mha_sublayer_matches_plain_torch(sp, tdt):
+    # Algorithm 5 as a module (LayerNorm, projections, heads, W^O, residual) against the same
+    # sub-layer written with dense masked attention in plain torch ops, forward and all gradients
+    block, nb, B, H = 32, 4, 2, 2
+    L, D = nb * block, 64 * H
+    torch.manual_seed(1)
+    fl = si.random_block_mask(nb, 0.5, seed=7)
+    pat = _pattern_from_mask(sp, fl, block)
+    mha = sp.SparseMHA(D, H, dropout=0.0, device="cuda", dtype=tdt)
+    E = torch.randn(B, L, D, device="cuda", dtype=tdt, requires_grad=True)
+    dOut = torch.randn(B, L, D, device="cuda", dtype=tdt)
+    out = mha(E, pat)
+    out.backward(dOut)
+    got = [out.detach().float(), E.grad.float().clone()] + [p.grad.float().clone() for p in mha.parameters()]
+    E.grad = None
+    mha.zero_grad()
+
+    P = torch.from_numpy(oracle.upsample(fl, block)).cuda().bool()
+    X = mha.norm(E)
+    qkv = mha.w_qkv(X).view(B, L, 3, H, 64)
+    q, k, v = [qkv[:, :, i].transpose(1, 2).float() for i in range(3)]
+    a = torch.softmax((q @ k.transpose(-1, -2) / 8.0).masked_fill(~P, float("-inf")), dim=-1) @ v
+    ref_out = mha.w_o(a.to(tdt).transpose(1, 2).reshape(B, L, D)) + E
+    ref_out.backward(dOut)
+    ref = [ref_out.detach().float(), E.grad.float()] + [p.grad.float() for p in mha.parameters()]
+    tol = 1e-4 if tdt == torch.float32 else 3e-2
+    for g, r in zip(got, ref):
+        assert torch.isfinite(g).all()
+        assert float((g - r).norm() / r.norm()) < tol
+    mha.train()
+    drop = sp.SparseMHA(D, H, dropout=0.5, device="cuda", dtype=tdt)
+    assert drop(E.detach(), pat).shape == (B, L, D)
+
+
 def test_attention_backward_is_deterministic(sp):
     w = si.workload(2)
     Q, K, V, dO = si.make_qkv_do(w, bh_limit=8)
