@@ -119,13 +119,39 @@ __device__ __forceinline__ void stage_tile(const T* __restrict__ src, T* rm, T* 
     }
 }
 
+// Reductions over the four lanes r, r + 16, r + 32, r + 48 that hold values of the same owned row.
+// v_permlane16_swap / v_permlane32_swap exchange rows of 16 (halves of 32) lanes between two
+// registers in the VALU: with both registers holding v, one comes back as {row 0, row 0, row 2,
+// row 2} and the other as {row 1, row 1, row 3, row 3} (resp. low half twice / high half twice).
+// No LDS round trip, unlike a shuffle.  The two results pass through an empty asm statement: given
+// equal inputs the compiler otherwise treats them as equal and drops the combine.
+__device__ __forceinline__ void swap_rows16(float v, float& a, float& b) {
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    unsigned r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    a = __builtin_bit_cast(float, r0);
+    b = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ void swap_halves32(float v, float& a, float& b) {
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    unsigned r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    a = __builtin_bit_cast(float, r0);
+    b = __builtin_bit_cast(float, r1);
+}
 __device__ __forceinline__ float group_max(float v) {
-    v = fmaxf(v, __shfl_xor(v, 16));
-    return fmaxf(v, __shfl_xor(v, 32));
+    float a, b;
+    swap_rows16(v, a, b);
+    swap_halves32(fmaxf(a, b), a, b);
+    return fmaxf(a, b);
 }
 __device__ __forceinline__ float group_sum(float v) {
-    v += __shfl_xor(v, 16);
-    return v + __shfl_xor(v, 32);
+    float a, b;
+    swap_rows16(v, a, b);
+    swap_halves32(a + b, a, b);
+    return a + b;
 }
 
 template <typename T>
