@@ -19,6 +19,19 @@
 
 namespace spion {
 
+// Developer build only (-DSPION_KERNEL_TRACE): workgroup timestamps of pipeline stages, 16 slots per
+// workgroup, written to a buffer the test harness installs with hipMemcpyToSymbol.
+#ifdef SPION_KERNEL_TRACE
+__device__ long long* spion_trace_buf = nullptr;
+void set_trace_buf(long long* p) { (void)hipMemcpyToSymbol(HIP_SYMBOL(spion_trace_buf), &p, sizeof(p)); }
+#define SPION_TP(slot)                                                                          \
+    do {                                                                                        \
+        if (threadIdx.x == 0 && spion_trace_buf) spion_trace_buf[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); \
+    } while (0)
+#else
+#define SPION_TP(slot) do { } while (0)
+#endif
+
 __device__ __forceinline__ bf16x4 lds_read_tr(const bf16_t* p) {
     typedef bf16x4 __attribute__((address_space(3))) * lds_ptr;
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)p);
@@ -134,13 +147,33 @@ __device__ __forceinline__ void stage_ready(int it, int n) {
 // order of the blocks changes the rounding of the sums only.)  pd = position of I among the row's
 // entries, or -1 if the row has no diagonal block: then the walk is in index order and the early
 // load is thrown away.
-__device__ __forceinline__ int find_in_row(const int* __restrict__ cols, int n, int I, int lane) {
-    for (int base = 0; base < n; base += 64) {
-        const int c = base + lane < n ? cols[base + lane] : -1;
-        const unsigned long long hit = __ballot(c == I);
-        if (hit) return base + __builtin_ctzll(hit);
+// Scalar loads on purpose: they do not count against the vector-memory counter, so waiting for
+// them does not wait for the tile loads already in flight.  The entries of a row ascend, so the scan
+// stops at the first entry >= I.  first[] receives entries 0..7 (clamped to the row), from which
+// the first blocks of the walk are taken without another dependent load.
+__device__ __forceinline__ int find_in_row(const int* __restrict__ cols, int n, int I, int (&first)[8]) {
+    const int last = n - 1;
+    int pd = -2;   // -2: not decided yet
+#pragma unroll
+    for (int e = 0; e < 8; ++e) first[e] = cols[e < last ? e : last];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (pd == -2 && first[e] >= I) pd = (first[e] == I && e < n) ? e : -1;
+    for (int base = 8; base < n && pd == -2; base += 8) {
+        int c[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c[e] = cols[base + e < last ? base + e : last];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (pd == -2 && c[e] >= I) pd = (c[e] == I && base + e < n) ? base + e : -1;
     }
-    return -1;
+    return pd == -2 ? -1 : pd;
+}
+__device__ __forceinline__ int pick8(const int (&v)[8], int i) {
+    const int a = (i & 1) ? v[1] : v[0], b = (i & 1) ? v[3] : v[2], c = (i & 1) ? v[5] : v[4],
+              d = (i & 1) ? v[7] : v[6];
+    const int ab = (i & 2) ? b : a, cd = (i & 2) ? d : c;
+    return (i & 4) ? cd : ab;
 }
 __device__ __forceinline__ int walk_index(int t, int pd) {
     return pd < 0 ? t : (t == 0 ? pd : (t - 1 < pd ? t - 1 : t));
@@ -153,6 +186,7 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     const int* __restrict__ col_idx, int L, int nb, int total, float scale_log2, int paper_denom) {
     constexpr int NKT = BS / 16, D = NS - 1;
     __shared__ __attribute__((aligned(16))) KvSmem<BS> sm0, sm1, sm2;   // sm2 unused (removed) for NS == 2
+    SPION_TP(0);
 
     const int vid = xcd_remap(blockIdx.x, total);
     const int I = vid % nb, bh = vid / nb;
@@ -171,15 +205,19 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
     const int last = n > 0 ? n - 1 : 0;
     const int* cols = col_idx + jb;
-    const int pd = __builtin_amdgcn_readfirstlane(find_in_row(cols, n, I, lane));
+    int first[8];
+    const int pd = n > 0 ? find_in_row(cols, n, I, first) : -1;
     // block visited at step t (clamped reads stay inside this row's entries; an empty row reads nothing)
-    auto col_at = [&](int t) { return cols[walk_index(t < last ? t : last, pd)]; };
+    auto col_at = [&](int t) {
+        const int j = walk_index(t < last ? t : last, pd);
+        return j < 8 ? pick8(first, j) : cols[j];
+    };
     if (pd < 0 && n > 0) {
         // no diagonal block in this row: once everyone's early load has landed, load block 0 over it
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        issue(sm0, cols[0]);
+        issue(sm0, first[0]);
     }
     if (D > 1 && n > 1) issue(sm1, col_at(1));
     int Jpre = n > 0 ? col_at(D) : 0;   // block of step it + D
@@ -199,7 +237,9 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)1.0f;
 
     auto step = [&](const KvSmem<BS>& cur, KvSmem<BS>& tgt, int it) {
+        if (it < 6) SPION_TP(2 + 2 * it);
         stage_ready<NS>(it, n);
+        if (it < 6) SPION_TP(3 + 2 * it);
         if (it + D < n) issue(tgt, Jpre);
         Jpre = col_at(it + D + 1);
         // S^T tile kt: [key 16 kt + 4 g + i][query r]
@@ -266,9 +306,11 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     }
     const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
     bf16_t* orow = O + head + (size_t)qrow * kD;
+    SPION_TP(14);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) store_quad<bf16_t>(orow + dt * 16 + 4 * g, oacc[dt] * inv);
     if (g == 0) LSE[(size_t)bh * L + qrow] = lsum > 0.f ? (m + log2f(lsum)) * kLn2 : -INFINITY;
+    SPION_TP(15);
 }
 
 template <int BS, int NS>
@@ -299,15 +341,19 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
     const int last = n > 0 ? n - 1 : 0;
     const int* cols = col_idx + jb;
-    const int pd = __builtin_amdgcn_readfirstlane(find_in_row(cols, n, I, lane));
+    int first[8];
+    const int pd = n > 0 ? find_in_row(cols, n, I, first) : -1;
     // block visited at step t (clamped reads stay inside this row's entries; an empty row reads nothing)
-    auto col_at = [&](int t) { return cols[walk_index(t < last ? t : last, pd)]; };
+    auto col_at = [&](int t) {
+        const int j = walk_index(t < last ? t : last, pd);
+        return j < 8 ? pick8(first, j) : cols[j];
+    };
     if (pd < 0 && n > 0) {
         // no diagonal block in this row: once everyone's early load has landed, load block 0 over it
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        issue(sm0, cols[0]);
+        issue(sm0, first[0]);
     }
     if (D > 1 && n > 1) issue(sm1, col_at(1));
     int Jpre = n > 0 ? col_at(D) : 0;   // block of step it + D
