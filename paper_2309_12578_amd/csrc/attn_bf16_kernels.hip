@@ -119,7 +119,10 @@ __device__ __forceinline__ void mma_over_rows_swz(f32x4 (&acc)[4], const bf16_t*
 }
 
 // ------------------------------------------------------------------------------------------------
-// forward and backward query side: K / V tiles in NS stages (prefetch distance NS - 1 blocks)
+// forward and backward query side: K / V tiles in two LDS stages, the next block loading while the
+// current one is multiplied.  Two stages of {K, V} are 32 KB at block 64; four workgroups share a CU
+// with up to 40 KB each.  (A third stage is 48 KB, i.e. three workgroups per CU, and measured 5-10 %
+// slower; three K stages + two V stages with a second barrier per block measured 4 % slower.)
 // ------------------------------------------------------------------------------------------------
 template <int BS>
 struct KvSmem {
@@ -127,14 +130,11 @@ struct KvSmem {
     bf16_t v[BS * kD];
 };
 
-// Wait until this wave's loads of block `it` have landed (the younger groups, 4 loads each, may stay
-// in flight), then meet the other waves: their parts have landed too and nobody reads the stage of
-// block it - 1 any more.  A bare barrier: the fences of __syncthreads would wait for every load in
-// flight, the prefetched blocks included.
-template <int NS>
-__device__ __forceinline__ void stage_ready(int it, int n) {
-    if (NS == 3 && it > 0 && it + 1 < n) __builtin_amdgcn_s_waitcnt(kWaitVm4);
-    else __builtin_amdgcn_s_waitcnt(kWaitVm0);   // step 0 also waits for the owned-row fragments
+// Wait until this wave's loads of the current block have landed (nothing younger is in flight at this
+// point), then meet the other waves: their parts have landed too and nobody reads the other stage
+// any more.  A bare barrier: __syncthreads adds fences the kernel has no use for.
+__device__ __forceinline__ void stage_ready() {
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
@@ -179,13 +179,13 @@ __device__ __forceinline__ int walk_index(int t, int pd) {
     return pd < 0 ? t : (t == 0 ? pd : (t - 1 < pd ? t - 1 : t));
 }
 
-template <int BS, int NS>
+template <int BS>
 __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE, const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, int L, int nb, int total, float scale_log2, int paper_denom) {
-    constexpr int NKT = BS / 16, D = NS - 1;
-    __shared__ __attribute__((aligned(16))) KvSmem<BS> sm0, sm1, sm2;   // sm2 unused (removed) for NS == 2
+    constexpr int NKT = BS / 16;
+    __shared__ __attribute__((aligned(16))) KvSmem<BS> sm0, sm1;
     SPION_TP(0);
 
     const int vid = xcd_remap(blockIdx.x, total);
@@ -219,8 +219,7 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         asm volatile("" ::: "memory");
         issue(sm0, first[0]);
     }
-    if (D > 1 && n > 1) issue(sm1, col_at(1));
-    int Jpre = n > 0 ? col_at(D) : 0;   // block of step it + D
+    int Jnext = n > 0 ? col_at(1) : 0;   // block of step it + 1
 
     bf16x8 qf[2];
 #pragma unroll
@@ -238,10 +237,10 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
 
     auto step = [&](const KvSmem<BS>& cur, KvSmem<BS>& tgt, int it) {
         if (it < 6) SPION_TP(2 + 2 * it);
-        stage_ready<NS>(it, n);
+        stage_ready();
         if (it < 6) SPION_TP(3 + 2 * it);
-        if (it + D < n) issue(tgt, Jpre);
-        Jpre = col_at(it + D + 1);
+        if (it + 1 < n) issue(tgt, Jnext);
+        Jnext = col_at(it + 2);
         // S^T tile kt: [key 16 kt + 4 g + i][query r]
         f32x4 s[NKT];
         float mx = -INFINITY;
@@ -277,17 +276,9 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         mma_over_rows_swz<BS>(oacc, cur.v, pq, sl);   // O^T[d][query] += V^T P^T
     };
 
-    if constexpr (NS == 3) {
-        for (int it = 0; it < n; it += 3) {
-            step(sm0, sm2, it);
-            if (it + 1 < n) step(sm1, sm0, it + 1);
-            if (it + 2 < n) step(sm2, sm1, it + 2);
-        }
-    } else {
-        for (int it = 0; it < n; it += 2) {
-            step(sm0, sm1, it);
-            if (it + 1 < n) step(sm1, sm0, it + 1);
-        }
+    for (int it = 0; it < n; it += 2) {
+        step(sm0, sm1, it);
+        if (it + 1 < n) step(sm1, sm0, it + 1);
     }
 
     // an empty row never waited for its early load: it must land before this workgroup's LDS is freed
@@ -313,7 +304,7 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     SPION_TP(15);
 }
 
-template <int BS, int NS>
+template <int BS>
 __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, const float* __restrict__ LSE,
@@ -321,8 +312,8 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     const int* __restrict__ col_idx, const int* __restrict__ col_ptr, int w_max, int split_max,
     int4* __restrict__ sched, int4* __restrict__ split, int L, int nb, int total, float scale,
     float scale_log2) {
-    constexpr int NKT = BS / 16, D = NS - 1;
-    __shared__ __attribute__((aligned(16))) KvSmem<BS> sm0, sm1, sm2;
+    constexpr int NKT = BS / 16;
+    __shared__ __attribute__((aligned(16))) KvSmem<BS> sm0, sm1;
 
     const int vid = xcd_remap(blockIdx.x, total);
     const int I = vid % nb, bh = vid / nb;
@@ -355,8 +346,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
         asm volatile("" ::: "memory");
         issue(sm0, first[0]);
     }
-    if (D > 1 && n > 1) issue(sm1, col_at(1));
-    int Jpre = n > 0 ? col_at(D) : 0;   // block of step it + D
+    int Jnext = n > 0 ? col_at(1) : 0;   // block of step it + 1
 
     if (vid == 0 && tid < 64) build_key_schedule(col_ptr, nb, w_max, split_max, sched, split, tid);
 
@@ -380,9 +370,9 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     for (int dt = 0; dt < 4; ++dt) dq[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     auto step = [&](const KvSmem<BS>& cur, KvSmem<BS>& tgt, int it) {
-        stage_ready<NS>(it, n);
-        if (it + D < n) issue(tgt, Jpre);
-        Jpre = col_at(it + D + 1);
+        stage_ready();
+        if (it + 1 < n) issue(tgt, Jnext);
+        Jnext = col_at(it + 2);
         bf16x4 dsq[NKT];
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
@@ -404,17 +394,9 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
         mma_over_rows_swz<BS>(dq, cur.k, dsq, sl);    // dQ^T[d][query] += K^T dS^T
     };
 
-    if constexpr (NS == 3) {
-        for (int it = 0; it < n; it += 3) {
-            step(sm0, sm2, it);
-            if (it + 1 < n) step(sm1, sm0, it + 1);
-            if (it + 2 < n) step(sm2, sm1, it + 2);
-        }
-    } else {
-        for (int it = 0; it < n; it += 2) {
-            step(sm0, sm1, it);
-            if (it + 1 < n) step(sm1, sm0, it + 1);
-        }
+    for (int it = 0; it < n; it += 2) {
+        step(sm0, sm1, it);
+        if (it + 1 < n) step(sm1, sm0, it + 1);
     }
     // an empty row never waited for its early load: it must land before this workgroup's LDS is freed
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
@@ -562,16 +544,6 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
     }
 }
 
-// LDS stages of the row-walking kernels.  Two stages of {K, V} are 32 KB at block 64, the most that
-// still lets four workgroups share a CU; a third stage (prefetch distance 2) costs the fourth
-// workgroup and measured no faster.  Developer builds may override.
-#ifndef SPION_FWD_STAGES
-#define SPION_FWD_STAGES 2
-#endif
-#ifndef SPION_DQ_STAGES
-#define SPION_DQ_STAGES 2
-#endif
-constexpr int kFwdStages = SPION_FWD_STAGES, kDqStages = SPION_DQ_STAGES;
 
 // ------------------------------------------------------------------------------------------------
 // launchers (called by the dispatch in attn_kernels.hip)
@@ -580,7 +552,7 @@ template <int BS>
 hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, void* O, float* LSE,
                     const int* row_ptr, const int* col_idx, hipStream_t st) {
     const int total = s.nb * s.BH;
-    attn_fwd_bf16_kernel<BS, kFwdStages><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+    attn_fwd_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
         static_cast<bf16_t*>(O), LSE, row_ptr, col_idx, s.L, s.nb, total, s.scale * kLog2e, s.paper_denom);
     return hipGetLastError();
@@ -592,7 +564,7 @@ hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const v
                        const int* col_idx, const int* col_ptr, int w_max, int split_max, int4* sched,
                        int4* split, hipStream_t st) {
     const int total = s.nb * s.BH;
-    attn_bwd_dq_bf16_kernel<BS, kDqStages><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
+    attn_bwd_dq_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
         static_cast<const bf16_t*>(O), static_cast<const bf16_t*>(dO), LSE, static_cast<bf16_t*>(dQ), delta,
         row_ptr, col_idx, col_ptr, w_max, split_max, sched, split, s.L, s.nb, total, s.scale,
