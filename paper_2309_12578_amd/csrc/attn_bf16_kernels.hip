@@ -430,9 +430,23 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
     // separate objects, so that the compiler can tell a read of one stage from a load in flight into
     // another and does not wait for it
     __shared__ __attribute__((aligned(16))) DkvSmem<BS> sm0, sm1, sm2;
+    SPION_TP(0);
 
-    const int vid = xcd_remap(blockIdx.x, total);
-    const int w = vid % w_max, bh = vid / w_max;
+    // Work item w of head bh.  Each XCD works on whole heads (so a head's Q / dO stay in one L2), and
+    // within an XCD the ids go item-major: the long items (low w) of all its heads are dispatched
+    // before any short one, instead of one head's short items ahead of the next head's long ones.
+    int w, bh;
+    {
+        const int BH = total / w_max;
+        if ((BH & 7) == 0) {
+            const int hpx = BH >> 3, x = blockIdx.x & 7, l = blockIdx.x >> 3;   // l-th workgroup of XCD x
+            bh = x * hpx + l % hpx;
+            w = l / hpx;
+        } else {
+            bh = blockIdx.x % BH;
+            w = blockIdx.x / BH;
+        }
+    }
     const int4 item = sched[w];
     const int J = item.x, n = item.z - item.y, slot = item.w;
     if (J < 0) return;
@@ -478,7 +492,9 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
         dv[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
+    SPION_TP(1);
     auto step = [&](const DkvSmem<BS>& cur, DkvSmem<BS>& nxt2, int it) {
+        if (it < 6) SPION_TP(2 + 2 * it);
         // wait until this wave's part of block `it` has landed; the group of block it + 1 may fly on
         if (it + 1 < n && it > 0) {
             if (wave < 2) __builtin_amdgcn_s_waitcnt(kWaitVm5);
@@ -492,6 +508,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+        if (it < 6) SPION_TP(3 + 2 * it);
         if (it + 2 < n) issue(nxt2, Ipre);
         Ipre = rows[it + 3 < last ? it + 3 : last];
         bf16x4 pq[NQT], dsq[NQT];
@@ -524,6 +541,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
         if (it + 2 < n) step(sm2, sm1, it + 2);
     }
 
+    SPION_TP(14);
     if (slot < 0) {
         bf16_t* dkrow = dK + head + (size_t)krow * kD;
         bf16_t* dvrow = dV + head + (size_t)krow * kD;
@@ -542,6 +560,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
             *reinterpret_cast<f32x4*>(pv + dt * 16 + 4 * g) = dv[dt];
         }
     }
+    SPION_TP(15);
 }
 
 
