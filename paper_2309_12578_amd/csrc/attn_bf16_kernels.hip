@@ -309,9 +309,9 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, const float* __restrict__ LSE,
     bf16_t* __restrict__ dQ, float* __restrict__ delta_out, const int* __restrict__ row_ptr,
-    const int* __restrict__ col_idx, const int* __restrict__ col_ptr, int w_max, int split_max,
-    int4* __restrict__ sched, int4* __restrict__ split, int L, int nb, int total, float scale,
-    float scale_log2) {
+    const int* __restrict__ col_idx, const int* __restrict__ col_ptr, const int* __restrict__ row_idx,
+    int w_max, int split_max, int4* __restrict__ sched, int4* __restrict__ split, int L, int nb, int total,
+    float scale, float scale_log2) {
     constexpr int NKT = BS / 16;
     __shared__ __attribute__((aligned(16))) KvSmem<BS> sm0, sm1;
 
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     }
     int Jnext = n > 0 ? col_at(1) : 0;   // block of step it + 1
 
-    if (vid == 0 && tid < 64) build_key_schedule(col_ptr, nb, w_max, split_max, sched, split, tid);
+    if (vid == 0 && tid < 64) build_key_schedule(col_ptr, row_idx, nb, w_max, split_max, sched, split, tid);
 
     bf16x8 qf[2], dof[2];
     float delta = 0.f;
@@ -447,7 +447,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
             w = blockIdx.x / BH;
         }
     }
-    const int4 item = sched[w];
+    const int4 item = sched[w], fr = sched[w_max + w];   // the item and its first four block rows
     const int J = item.x, n = item.z - item.y, slot = item.w;
     if (J < 0) return;
     const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, g = lane >> 4;
@@ -473,9 +473,9 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
         }
     };
 
-    int Ipre = n > 0 ? rows[2 < last ? 2 : last] : 0;   // block of step it + 2
-    if (n > 0) issue(sm0, rows[0]);
-    if (n > 1) issue(sm1, rows[1]);
+    int Ipre = fr.z;   // block of step it + 2
+    if (n > 0) issue(sm0, fr.x);
+    if (n > 1) issue(sm1, fr.y);
     // owned K / V fragments (step 0 waits for everything issued up to here)
     bf16x8 kf[2], vf[2];
 #pragma unroll
@@ -510,7 +510,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
         asm volatile("" ::: "memory");
         if (it < 6) SPION_TP(3 + 2 * it);
         if (it + 2 < n) issue(nxt2, Ipre);
-        Ipre = rows[it + 3 < last ? it + 3 : last];
+        Ipre = it == 0 ? fr.w : rows[it + 3 < last ? it + 3 : last];
         bf16x4 pq[NQT], dsq[NQT];
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
@@ -580,13 +580,13 @@ hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void
 template <int BS>
 hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
                        const void* dO, const float* LSE, void* dQ, float* delta, const int* row_ptr,
-                       const int* col_idx, const int* col_ptr, int w_max, int split_max, int4* sched,
-                       int4* split, hipStream_t st) {
+                       const int* col_idx, const int* col_ptr, const int* row_idx, int w_max, int split_max,
+                       int4* sched, int4* split, hipStream_t st) {
     const int total = s.nb * s.BH;
     attn_bwd_dq_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
         static_cast<const bf16_t*>(O), static_cast<const bf16_t*>(dO), LSE, static_cast<bf16_t*>(dQ), delta,
-        row_ptr, col_idx, col_ptr, w_max, split_max, sched, split, s.L, s.nb, total, s.scale,
+        row_ptr, col_idx, col_ptr, row_idx, w_max, split_max, sched, split, s.L, s.nb, total, s.scale,
         s.scale * kLog2e);
     return hipGetLastError();
 }
@@ -609,10 +609,10 @@ template hipError_t fwd_bf16<64>(const AttnShape&, const void*, const void*, con
                                  const int*, const int*, hipStream_t);
 template hipError_t bwd_dq_bf16<32>(const AttnShape&, const void*, const void*, const void*, const void*,
                                     const void*, const float*, void*, float*, const int*, const int*,
-                                    const int*, int, int, int4*, int4*, hipStream_t);
+                                    const int*, const int*, int, int, int4*, int4*, hipStream_t);
 template hipError_t bwd_dq_bf16<64>(const AttnShape&, const void*, const void*, const void*, const void*,
                                     const void*, const float*, void*, float*, const int*, const int*,
-                                    const int*, int, int, int4*, int4*, hipStream_t);
+                                    const int*, const int*, int, int, int4*, int4*, hipStream_t);
 template hipError_t bwd_dkv_bf16<32>(const AttnShape&, const void*, const void*, const void*, const void*,
                                      const float*, const float*, void*, void*, const int*, const int4*,
                                      int, int, float*, hipStream_t);

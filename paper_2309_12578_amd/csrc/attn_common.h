@@ -168,6 +168,8 @@ __device__ __forceinline__ void store_quad(T* dst, f32x4 v) {
 // for every head; one wave of the query-side kernel (which always runs first) builds it.
 //   sched[w]   = {J, kb, ke, slot}: BSC entries [kb, ke) of column J; slot < 0: write final output;
 //                J < 0: unused work item
+//   sched[w_max + w] = the first four block rows of the item, row_idx[kb .. kb + 3] clamped to the
+//                item: a workgroup gets them with the item in one round trip instead of two
 //   split[m]   = {J, first slot, nch, 0} for the m-th split column; J < 0: unused entry
 // ------------------------------------------------------------------------------------------------
 #ifndef SPION_KEY_CHUNK
@@ -188,8 +190,9 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
     return v;
 }
 
-__device__ void build_key_schedule(const int* __restrict__ col_ptr, int nb, int w_max, int split_max,
-                                   int4* __restrict__ sched, int4* __restrict__ split, int lane) {
+__device__ void build_key_schedule(const int* __restrict__ col_ptr, const int* __restrict__ row_idx, int nb,
+                                   int w_max, int split_max, int4* __restrict__ sched,
+                                   int4* __restrict__ split, int lane) {
     // Two passes: the chunks of split columns (the longest work items) get the lowest work item
     // numbers and so start first; columns that fit one work item follow.
     int run_w = 0, run_s = 0, run_m = 0;
@@ -208,9 +211,16 @@ __device__ void build_key_schedule(const int* __restrict__ col_ptr, int nb, int 
             const int w0 = run_w + w_incl - nch, s0 = run_s + s_incl - ns, m0 = run_m + m_incl - is_split;
             if (mine) {
                 if (is_split && m0 < split_max) split[m0] = make_int4(J, s0, nch, 0);
-                for (int ci = 0; ci < nch && w0 + ci < w_max; ++ci)
-                    sched[w0 + ci] = make_int4(J, c0 + (ci * cnt) / nch, c0 + ((ci + 1) * cnt) / nch,
-                                               nch > 1 ? s0 + ci : -1);
+                for (int ci = 0; ci < nch && w0 + ci < w_max; ++ci) {
+                    const int kb = c0 + (ci * cnt) / nch, ke = c0 + ((ci + 1) * cnt) / nch;
+                    sched[w0 + ci] = make_int4(J, kb, ke, nch > 1 ? s0 + ci : -1);
+                    int fr[4] = {0, 0, 0, 0};
+                    if (ke > kb) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) fr[e] = row_idx[kb + e < ke - 1 ? kb + e : ke - 1];
+                    }
+                    sched[w_max + w0 + ci] = make_int4(fr[0], fr[1], fr[2], fr[3]);
+                }
             }
             run_w += __shfl(w_incl, 63);
             run_s += __shfl(s_incl, 63);

@@ -123,11 +123,11 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ O,
     const T* __restrict__ dO, const float* __restrict__ LSE, T* __restrict__ dQ,
     float* __restrict__ delta_out, const int* __restrict__ row_ptr, const int* __restrict__ col_idx,
-    const int* __restrict__ col_ptr, int w_max, int split_max, int4* __restrict__ sched,
-    int4* __restrict__ split,
+    const int* __restrict__ col_ptr, const int* __restrict__ row_idx, int w_max, int split_max,
+    int4* __restrict__ sched, int4* __restrict__ split,
     int L, int nb, float scale, float scale_log2) {
     if (blockIdx.x == 0 && threadIdx.x < 64)
-        build_key_schedule(col_ptr, nb, w_max, split_max, sched, split, threadIdx.x);
+        build_key_schedule(col_ptr, row_idx, nb, w_max, split_max, sched, split, threadIdx.x);
     typedef typename Elem<T>::Frag Frag;
     typedef typename Elem<T>::Quad Quad;
     constexpr int EPL = Elem<T>::EPL, KC = Elem<T>::KC, NDC = kD / KC, NKT = BS / 16;
@@ -328,7 +328,7 @@ BwdWorkspace::BwdWorkspace(int BH, int L, int bs, int nb, int nnzb) {
     delta_off = 0;
     sched_off = delta_off + up((size_t)BH * L * sizeof(float));
     split_max = key_split_max(nnzb);
-    split_off = sched_off + up((size_t)w_max * sizeof(int4));
+    split_off = sched_off + up((size_t)2 * w_max * sizeof(int4));   // items, then their first rows
     partial_off = split_off + up((size_t)split_max * sizeof(int4));
     total = partial_off + up((size_t)BH * n_slots * 2 * bs * kD * sizeof(float));
 }
@@ -359,14 +359,14 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
     if constexpr (kTuned) {
         if (s.bwd_phases & 1) {
             const hipError_t e = bwd_dq_bf16<BS>(s, Q, K, V, O, dO, LSE, dQ, delta, row_ptr, col_idx, col_ptr,
-                                                 ws.w_max, ws.split_max, sched, split, st);
+                                                 row_idx, ws.w_max, ws.split_max, sched, split, st);
             if (e != hipSuccess) return e;
         }
     } else if (s.bwd_phases & 1) {
         attn_bwd_dq_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
             static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
             static_cast<const T*>(O), static_cast<const T*>(dO), LSE, static_cast<T*>(dQ), delta,
-            row_ptr, col_idx, col_ptr, ws.w_max, ws.split_max, sched, split, s.L, s.nb, s.scale,
+            row_ptr, col_idx, col_ptr, row_idx, ws.w_max, ws.split_max, sched, split, s.L, s.nb, s.scale,
             s.scale * kLog2e);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -52,8 +52,8 @@ hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void
 template <int BS>
 hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
                        const void* dO, const float* LSE, void* dQ, float* delta, const int* row_ptr,
-                       const int* col_idx, const int* col_ptr, int w_max, int split_max, int4* sched,
-                       int4* split, hipStream_t st);
+                       const int* col_idx, const int* col_ptr, const int* row_idx, int w_max, int split_max,
+                       int4* sched, int4* split, hipStream_t st);
 template <int BS>
 hipError_t bwd_dkv_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* dO,
                         const float* LSE, const float* delta, void* dK, void* dV, const int* row_idx,
