@@ -130,11 +130,13 @@ struct KvSmem {
     bf16_t v[BS * kD];
 };
 
-// Wait until this wave's loads of the current block have landed (nothing younger is in flight at this
-// point), then meet the other waves: their parts have landed too and nobody reads the other stage
-// any more.  A bare barrier: __syncthreads adds fences the kernel has no use for.
-__device__ __forceinline__ void stage_ready() {
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+// Wait until this wave's loads of the current block have landed, then meet the other waves: their
+// parts have landed too and nobody reads the other stage any more.  younger_in_flight: the block
+// after this one was already requested (only at step 0, from the prologue) and may stay in flight.
+// A bare barrier: __syncthreads adds fences the kernel has no use for.
+__device__ __forceinline__ void stage_ready(bool younger_in_flight) {
+    if (younger_in_flight) __builtin_amdgcn_s_waitcnt(kWaitVm4);
+    else __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
@@ -202,6 +204,10 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         tile_load_async(V + head + (size_t)J * BS * kD, st.v, wave, tl);
     };
     issue(sm0, I);   // the diagonal block, before any index is known
+    bf16x8 qf[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+        qf[c] = *reinterpret_cast<const bf16x8*>(Q + head + (size_t)qrow * kD + c * 32 + g * 8);
     const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
     const int last = n > 0 ? n - 1 : 0;
     const int* cols = col_idx + jb;
@@ -219,12 +225,9 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         asm volatile("" ::: "memory");
         issue(sm0, first[0]);
     }
-    int Jnext = n > 0 ? col_at(1) : 0;   // block of step it + 1
-
-    bf16x8 qf[2];
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-        qf[c] = *reinterpret_cast<const bf16x8*>(Q + head + (size_t)qrow * kD + c * 32 + g * 8);
+    // the second block goes out as soon as its index is known; it is the youngest load from here on
+    if (n > 1) issue(sm1, col_at(1));
+    int Jnext = n > 0 ? col_at(2) : 0;   // block of step it + 1, for it >= 1
 
     float m = -INFINITY;   // running row maximum in log2 units (score * scale * log2 e)
     f32x4 lacc = f32x4{0.f, 0.f, 0.f, 0.f};   // running row sum, replicated in its 4 elements
@@ -237,10 +240,14 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
 
     auto step = [&](const KvSmem<BS>& cur, KvSmem<BS>& tgt, int it) {
         if (it < 6) SPION_TP(2 + 2 * it);
-        stage_ready();
+        // loads in flight here: block `it`, and at step 0 also block 1, requested by the prologue (the
+        // four youngest loads: whatever else the prologue stored or loaded after them only adds waiting)
+        stage_ready(it == 0 && n > 1);
         if (it < 6) SPION_TP(3 + 2 * it);
-        if (it + 1 < n) issue(tgt, Jnext);
-        Jnext = col_at(it + 2);
+        if (it > 0) {
+            if (it + 1 < n) issue(tgt, Jnext);
+            Jnext = col_at(it + 2);
+        }
         // S^T tile kt: [key 16 kt + 4 g + i][query r]
         f32x4 s[NKT];
         float mx = -INFINITY;
@@ -329,6 +336,15 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
         tile_load_async(V + head + (size_t)J * BS * kD, st.v, wave, tl);
     };
     issue(sm0, I);   // the diagonal block, before any index is known
+    bf16x8 qf[2], dof[2], of[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const size_t off = head + (size_t)qrow * kD + c * 32 + g * 8;
+        qf[c] = *reinterpret_cast<const bf16x8*>(Q + off);
+        dof[c] = *reinterpret_cast<const bf16x8*>(dO + off);
+        of[c] = *reinterpret_cast<const bf16x8*>(O + off);
+    }
+    const float lse2 = LSE[(size_t)bh * L + qrow] * kLog2e;
     const int jb = row_ptr[I], n = row_ptr[I + 1] - jb;
     const int last = n > 0 ? n - 1 : 0;
     const int* cols = col_idx + jb;
@@ -346,33 +362,30 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
         asm volatile("" ::: "memory");
         issue(sm0, first[0]);
     }
-    int Jnext = n > 0 ? col_at(1) : 0;   // block of step it + 1
+    // the second block goes out as soon as its index is known
+    if (n > 1) issue(sm1, col_at(1));
+    int Jnext = n > 0 ? col_at(2) : 0;   // block of step it + 1, for it >= 1
 
     if (vid == 0 && tid < 64) build_key_schedule(col_ptr, row_idx, nb, w_max, split_max, sched, split, tid);
 
-    bf16x8 qf[2], dof[2];
     float delta = 0.f;
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const size_t off = head + (size_t)qrow * kD + c * 32 + g * 8;
-        qf[c] = *reinterpret_cast<const bf16x8*>(Q + off);
-        dof[c] = *reinterpret_cast<const bf16x8*>(dO + off);
-        const bf16x8 of = *reinterpret_cast<const bf16x8*>(O + off);
+    for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) delta = fmaf((float)dof[c][e], (float)of[e], delta);
-    }
+        for (int e = 0; e < 8; ++e) delta = fmaf((float)dof[c][e], (float)of[c][e], delta);
     delta = group_sum(delta);
     if (g == 0) delta_out[(size_t)bh * L + qrow] = delta;
-    const float lse2 = LSE[(size_t)bh * L + qrow] * kLog2e;
 
     f32x4 dq[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) dq[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     auto step = [&](const KvSmem<BS>& cur, KvSmem<BS>& tgt, int it) {
-        stage_ready();
-        if (it + 1 < n) issue(tgt, Jnext);
-        Jnext = col_at(it + 2);
+        stage_ready(it == 0 && n > 1);   // see the forward kernel
+        if (it > 0) {
+            if (it + 1 < n) issue(tgt, Jnext);
+            Jnext = col_at(it + 2);
+        }
         bf16x4 dsq[NKT];
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
