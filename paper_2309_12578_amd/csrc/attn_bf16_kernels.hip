@@ -226,7 +226,7 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         issue(sm0, first[0]);
     }
     // the second block goes out as soon as its index is known; it is the youngest load from here on
-    if (n > 1) issue(sm1, col_at(1));
+    if (n > 0) issue(sm1, col_at(1));   // (a one-block row loads its block twice: keeps the wait below uniform)
     int Jnext = n > 0 ? col_at(2) : 0;   // block of step it + 1, for it >= 1
 
     float m = -INFINITY;   // running row maximum in log2 units (score * scale * log2 e)
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         if (it < 6) SPION_TP(2 + 2 * it);
         // loads in flight here: block `it`, and at step 0 also block 1, requested by the prologue (the
         // four youngest loads: whatever else the prologue stored or loaded after them only adds waiting)
-        stage_ready(it == 0 && n > 1);
+        stage_ready(it == 0);
         if (it < 6) SPION_TP(3 + 2 * it);
         if (it > 0) {
             if (it + 1 < n) issue(tgt, Jnext);
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
         issue(sm0, first[0]);
     }
     // the second block goes out as soon as its index is known
-    if (n > 1) issue(sm1, col_at(1));
+    if (n > 0) issue(sm1, col_at(1));   // (a one-block row loads its block twice: keeps the wait below uniform)
     int Jnext = n > 0 ? col_at(2) : 0;   // block of step it + 1, for it >= 1
 
     if (vid == 0 && tid < 64) build_key_schedule(col_ptr, row_idx, nb, w_max, split_max, sched, split, tid);
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     for (int dt = 0; dt < 4; ++dt) dq[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     auto step = [&](const KvSmem<BS>& cur, KvSmem<BS>& tgt, int it) {
-        stage_ready(it == 0 && n > 1);   // see the forward kernel
+        stage_ready(it == 0);   // see the forward kernel
         if (it > 0) {
             if (it + 1 < n) issue(tgt, Jnext);
             Jnext = col_at(it + 2);
