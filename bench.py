@@ -17,7 +17,8 @@ profile is on file) and `roofline_mfma`; `path` (whole-step fractions, warm timi
 (per-layer kernel times); `pattern` (spion_pattern timing); `density_sweep` (the same step on random
 block masks of 2-30 % density, made by the no-fill variant of spion_pattern); `producers` (score-map
 mean and Frobenius distance); `ceilings` (what a plain copy and a library bf16 GEMM reach on this
-GPU); `cpu_baseline` (the CPU oracle).
+GPU); `streaming_floor` (the time a plain device copy needs for each phase's algorithmic bytes at
+this size); `cpu_baseline` (the CPU oracle).
 """
 from __future__ import annotations
 
@@ -133,6 +134,26 @@ def extras(sp, acc, torch, dev, w, tdt, code, BH, esz):
     ms_gemm = event_ms(torch, lambda: torch.matmul(a, b), 10)
     out["ceilings"] = {"copy_GBps_read_plus_write": round(2 * (1 << 30) / (ms_copy * 1e-3) / 1e9, 1),
                        "gemm_bf16_8192_TFLOPs": round(2 * 8192.0 ** 3 / (ms_gemm * 1e-3) / 1e12, 1)}
+    # what moving each phase's algorithmic bytes costs at this size: one device copy per phase with the
+    # same byte count (half read, half written), source and destination rotating through 1 GiB so
+    # that they come from HBM, timed with events like the phases themselves
+    pool_a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    pool_b = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    floor = {}
+    for k in KERNELS:
+        half = acc.algorithmic_bytes(k, BH, L, d, esz) // 2 // 256 * 256
+        n_slots = (1 << 30) // half
+        state = {"i": 0}
+
+        def one(half=half, n_slots=n_slots, state=state):
+            o = (state["i"] % n_slots) * half
+            pool_b[o:o + half].copy_(pool_a[o:o + half])
+            state["i"] += 1
+
+        floor[k + "_us"] = round(event_ms(torch, one, 60) * 1e3, 2)
+    floor["step_us"] = round(sum(floor.values()), 2)
+    floor["what"] = "device copy of the same byte count per phase (half read, half written), from HBM"
+    out["streaming_floor"] = floor
     return out
 
 
