@@ -46,6 +46,8 @@ def parse_args():
                     help="rotating buffer sets per layer (0: enough to exceed the Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pattern-iters", type=int, default=20)
+    ap.add_argument("--preroll-ms", type=float, default=300.0,
+                    help="untimed steps run for this long before the warm-up steps")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the density sweep, the producer kernels and the measured ceilings")
     return ap.parse_args()
@@ -264,6 +266,12 @@ def main() -> int:
         return (time.perf_counter() - t0) * 1e3 / n_steps
 
     # ---------------------------------------------------------------- headline: cold, rotating sets
+    # untimed pre-roll: clocks, page tables and TLBs of all buffer sets settle (a few hundred steps
+    # measure ~3 % faster than the first ones on this GPU); then the W warm-up steps, then K timed
+    t_end = time.perf_counter() + args.preroll_ms * 1e-3
+    while time.perf_counter() < t_end:
+        run(50, True)
+        torch.cuda.synchronize()
     run(args.warmup, True)
     ms_cold = timed(args.steps, True)
     run(args.warmup, False)
