@@ -173,7 +173,7 @@ __device__ __forceinline__ void store_quad(T* dst, f32x4 v) {
 //   split[m]   = {J, first slot, nch, 0} for the m-th split column; J < 0: unused entry
 // ------------------------------------------------------------------------------------------------
 #ifndef SPION_KEY_CHUNK
-#define SPION_KEY_CHUNK 8   // kept rows per key-side work item (build-time tunable)
+#define SPION_KEY_CHUNK 10   // kept rows per key-side work item (build-time tunable; 8-12 measure alike)
 #endif
 constexpr int kChunk = SPION_KEY_CHUNK;
 

@@ -294,16 +294,17 @@ def test_attention_long_rows_find_their_diagonal(sp):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_tall_columns_are_split_into_chunks(sp, dtype):
-    # columns with more kept rows than one key-side work item takes (8): 9, 17 and 20 rows
-    block, nb, BH, d = 16, 20, 2, 64
+    # columns with more kept rows than one key-side work item takes (10): 36, 25, 21 and 11 rows
+    block, nb, BH, d = 16, 36, 2, 64
     L = nb * block
     rng = np.random.default_rng(11)
     Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), dtype)
                    for _ in range(4)]
     fl = np.eye(nb, dtype=np.uint8)
     fl[:, 4] = 1
-    fl[:17, 9] = 1
-    fl[11:, 15] = 1
+    fl[:25, 9] = 1
+    fl[15:, 15] = 1
+    fl[20:31, 30] = 1
     fl[3, :] = 1
     _run_attention_case(sp, Q, K, V, dO, fl, block, dtype)
 
