@@ -315,7 +315,8 @@ template <int BS>
 __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ O, const bf16_t* __restrict__ dO, const float* __restrict__ LSE,
-    bf16_t* __restrict__ dQ, float* __restrict__ delta_out, const int* __restrict__ row_ptr,
+    bf16_t* __restrict__ dQ, float* __restrict__ delta_out, float* __restrict__ lse2_out,
+    const int* __restrict__ row_ptr,
     const int* __restrict__ col_idx, const int* __restrict__ col_ptr, const int* __restrict__ row_idx,
     int w_max, int split_max, int4* __restrict__ sched, int4* __restrict__ split, int L, int nb, int total,
     float scale, float scale_log2) {
@@ -374,7 +375,10 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) delta = fmaf((float)dof[c][e], (float)of[c][e], delta);
     delta = group_sum(delta);
-    if (g == 0) delta_out[(size_t)bh * L + qrow] = delta;
+    if (g == 0) {
+        delta_out[(size_t)bh * L + qrow] = delta;
+        lse2_out[(size_t)bh * L + qrow] = lse2;   // LSE in log2 units: the key side needs no multiply
+    }
 
     f32x4 dq[4];
 #pragma unroll
@@ -435,7 +439,7 @@ struct DkvSmem {
 template <int BS>
 __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const bf16_t* __restrict__ dO, const float* __restrict__ LSE2, const float* __restrict__ delta,
     bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, const int* __restrict__ row_idx,
     const int4* __restrict__ sched, int w_max, int total, int n_slots, float* __restrict__ partial, int L,
     float scale, float scale_log2) {
@@ -479,7 +483,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
         tile_load_async(dO + head + (size_t)I * BS * kD, st.d, wave, tl);
         if (wave == 0) {
             if (lane < BS)
-                __builtin_amdgcn_global_load_lds(LSE + vec + (size_t)I * BS + lane, (lds_void_ptr)st.lse, 4, 0, 0);
+                __builtin_amdgcn_global_load_lds(LSE2 + vec + (size_t)I * BS + lane, (lds_void_ptr)st.lse, 4, 0, 0);
         } else if (wave == 1) {
             if (lane < BS)
                 __builtin_amdgcn_global_load_lds(delta + vec + (size_t)I * BS + lane, (lds_void_ptr)st.del, 4, 0, 0);
@@ -533,7 +537,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
                 s = mma_d(s, *reinterpret_cast<const bf16x8*>(cur.q + qt * 16 * kD + sl.frag[c]), kf[c]);    // S = Q K^T
                 dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(cur.d + qt * 16 * kD + sl.frag[c]), vf[c]);  // dP = dO V^T
             }
-            const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&cur.lse[qt * 16 + 4 * g]) * kLog2e;
+            const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&cur.lse[qt * 16 + 4 * g]);   // log2 units
             const f32x4 del4 = *reinterpret_cast<const f32x4*>(&cur.del[qt * 16 + 4 * g]);
             f32x4 p, ds;
 #pragma unroll
@@ -592,13 +596,13 @@ hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void
 
 template <int BS>
 hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
-                       const void* dO, const float* LSE, void* dQ, float* delta, const int* row_ptr,
+                       const void* dO, const float* LSE, void* dQ, float* delta, float* lse2, const int* row_ptr,
                        const int* col_idx, const int* col_ptr, const int* row_idx, int w_max, int split_max,
                        int4* sched, int4* split, hipStream_t st) {
     const int total = s.nb * s.BH;
     attn_bwd_dq_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
-        static_cast<const bf16_t*>(O), static_cast<const bf16_t*>(dO), LSE, static_cast<bf16_t*>(dQ), delta,
+        static_cast<const bf16_t*>(O), static_cast<const bf16_t*>(dO), LSE, static_cast<bf16_t*>(dQ), delta, lse2,
         row_ptr, col_idx, col_ptr, row_idx, w_max, split_max, sched, split, s.L, s.nb, total, s.scale,
         s.scale * kLog2e);
     return hipGetLastError();
@@ -606,12 +610,12 @@ hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const v
 
 template <int BS>
 hipError_t bwd_dkv_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* dO,
-                        const float* LSE, const float* delta, void* dK, void* dV, const int* row_idx,
+                        const float* lse2, const float* delta, void* dK, void* dV, const int* row_idx,
                         const int4* sched, int w_max, int n_slots, float* partial, hipStream_t st) {
     const int total = w_max * s.BH;
     attn_bwd_dkv_bf16_kernel<BS><<<dim3((unsigned)total), dim3(BS * 4), 0, st>>>(
         static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
-        static_cast<const bf16_t*>(dO), LSE, delta, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV),
+        static_cast<const bf16_t*>(dO), lse2, delta, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV),
         row_idx, sched, w_max, total, n_slots, partial, s.L, s.scale, s.scale * kLog2e);
     return hipGetLastError();
 }
@@ -621,10 +625,10 @@ template hipError_t fwd_bf16<32>(const AttnShape&, const void*, const void*, con
 template hipError_t fwd_bf16<64>(const AttnShape&, const void*, const void*, const void*, void*, float*,
                                  const int*, const int*, hipStream_t);
 template hipError_t bwd_dq_bf16<32>(const AttnShape&, const void*, const void*, const void*, const void*,
-                                    const void*, const float*, void*, float*, const int*, const int*,
+                                    const void*, const float*, void*, float*, float*, const int*, const int*,
                                     const int*, const int*, int, int, int4*, int4*, hipStream_t);
 template hipError_t bwd_dq_bf16<64>(const AttnShape&, const void*, const void*, const void*, const void*,
-                                    const void*, const float*, void*, float*, const int*, const int*,
+                                    const void*, const float*, void*, float*, float*, const int*, const int*,
                                     const int*, const int*, int, int, int4*, int4*, hipStream_t);
 template hipError_t bwd_dkv_bf16<32>(const AttnShape&, const void*, const void*, const void*, const void*,
                                      const float*, const float*, void*, void*, const int*, const int4*,

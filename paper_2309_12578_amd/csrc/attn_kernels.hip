@@ -326,7 +326,7 @@ BwdWorkspace::BwdWorkspace(int BH, int L, int bs, int nb, int nnzb) {
     w_max = key_work_items_max(nnzb, nb);
     n_slots = key_slots_max(nnzb);
     delta_off = 0;
-    sched_off = delta_off + up((size_t)BH * L * sizeof(float));
+    sched_off = delta_off + up((size_t)2 * BH * L * sizeof(float));   // delta, then LSE in log2 units
     split_max = key_split_max(nnzb);
     split_off = sched_off + up((size_t)2 * w_max * sizeof(int4));   // items, then their first rows
     partial_off = split_off + up((size_t)split_max * sizeof(int4));
@@ -351,6 +351,7 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
     const BwdWorkspace ws(s.BH, s.L, s.bs, s.nb, nnzb);
     char* base = static_cast<char*>(workspace);
     float* delta = reinterpret_cast<float*>(base + ws.delta_off);
+    float* lse2 = delta + (size_t)s.BH * s.L;   // written by the tuned query-side kernel for the key side
     int4* sched = reinterpret_cast<int4*>(base + ws.sched_off);
     int4* split = reinterpret_cast<int4*>(base + ws.split_off);
     float* partial = reinterpret_cast<float*>(base + ws.partial_off);
@@ -358,8 +359,8 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
     constexpr bool kTuned = sizeof(T) == 2 && BS >= 32;
     if constexpr (kTuned) {
         if (s.bwd_phases & 1) {
-            const hipError_t e = bwd_dq_bf16<BS>(s, Q, K, V, O, dO, LSE, dQ, delta, row_ptr, col_idx, col_ptr,
-                                                 row_idx, ws.w_max, ws.split_max, sched, split, st);
+            const hipError_t e = bwd_dq_bf16<BS>(s, Q, K, V, O, dO, LSE, dQ, delta, lse2, row_ptr, col_idx,
+                                                 col_ptr, row_idx, ws.w_max, ws.split_max, sched, split, st);
             if (e != hipSuccess) return e;
         }
     } else if (s.bwd_phases & 1) {
@@ -373,7 +374,7 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
     }
     if (s.bwd_phases & 2) {
         if constexpr (kTuned) {
-            const hipError_t e = bwd_dkv_bf16<BS>(s, Q, K, V, dO, LSE, delta, dK, dV, row_idx, sched, ws.w_max,
+            const hipError_t e = bwd_dkv_bf16<BS>(s, Q, K, V, dO, lse2, delta, dK, dV, row_idx, sched, ws.w_max,
                                                   ws.n_slots, partial, st);
             if (e != hipSuccess) return e;
         } else {

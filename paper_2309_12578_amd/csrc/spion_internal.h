@@ -51,12 +51,12 @@ hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void
                     const int* row_ptr, const int* col_idx, hipStream_t st);
 template <int BS>
 hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
-                       const void* dO, const float* LSE, void* dQ, float* delta, const int* row_ptr,
+                       const void* dO, const float* LSE, void* dQ, float* delta, float* lse2, const int* row_ptr,
                        const int* col_idx, const int* col_ptr, const int* row_idx, int w_max, int split_max,
                        int4* sched, int4* split, hipStream_t st);
 template <int BS>
 hipError_t bwd_dkv_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* dO,
-                        const float* LSE, const float* delta, void* dK, void* dV, const int* row_idx,
+                        const float* lse2, const float* delta, void* dK, void* dV, const int* row_idx,
                         const int4* sched, int w_max, int n_slots, float* partial, hipStream_t st);
 
 }  // namespace spion
