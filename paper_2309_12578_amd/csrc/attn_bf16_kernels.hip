@@ -376,7 +376,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
         for (int e = 0; e < 8; ++e) delta = fmaf((float)dof[c][e], (float)of[c][e], delta);
     delta = group_sum(delta);
     if (g == 0) {
-        delta_out[(size_t)bh * L + qrow] = delta;
+        delta_out[(size_t)bh * L + qrow] = -delta;   // stored negated: it seeds the dP accumulators
         lse2_out[(size_t)bh * L + qrow] = lse2;   // LSE in log2 units: the key side needs no multiply
     }
 
@@ -393,7 +393,8 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
         bf16x4 dsq[NKT];
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
-            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, dp = f32x4{0.f, 0.f, 0.f, 0.f};
+            // dP - delta comes out of the MFMA: the accumulator starts at -delta instead of 0
+            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, dp = f32x4{-delta, -delta, -delta, -delta};
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 const int off = kt * 16 * kD + sl.frag[c];
@@ -404,7 +405,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float p = fast_exp2(fmaf(s[i], scale_log2, -lse2));
-                ds[i] = p * (dp[i] - delta);
+                ds[i] = p * dp[i];
             }
             dsq[kt] = to_quad<bf16_t>(ds);
         }
@@ -531,19 +532,20 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
         bf16x4 pq[NQT], dsq[NQT];
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
-            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, dp = f32x4{0.f, 0.f, 0.f, 0.f};
+            // the query side stored -delta: as the initial accumulator it makes the MFMA return dP - delta
+            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+            f32x4 dp = *reinterpret_cast<const f32x4*>(&cur.del[qt * 16 + 4 * g]);
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 s = mma_d(s, *reinterpret_cast<const bf16x8*>(cur.q + qt * 16 * kD + sl.frag[c]), kf[c]);    // S = Q K^T
                 dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(cur.d + qt * 16 * kD + sl.frag[c]), vf[c]);  // dP = dO V^T
             }
             const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&cur.lse[qt * 16 + 4 * g]);   // log2 units
-            const f32x4 del4 = *reinterpret_cast<const f32x4*>(&cur.del[qt * 16 + 4 * g]);
             f32x4 p, ds;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 p[i] = fast_exp2(fmaf(s[i], scale_log2, -lse4[i]));
-                ds[i] = p[i] * (dp[i] - del4[i]);
+                ds[i] = p[i] * dp[i];
             }
             pq[qt] = to_quad<bf16_t>(p);
             dsq[qt] = to_quad<bf16_t>(ds);
