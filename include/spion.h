@@ -96,8 +96,9 @@ int spion_pattern(const float *A_s, const spion_pattern_params *p, uint8_t *fl_o
 
 /* spion_attn_params.flags */
 #define SPION_ATTN_PAPER_DENOM 1u /* add Algorithm 6's exp(-max) * (L - kept) term to the row sum */
-/* spion_attn_bwd only: run one of its two kernels (for per-kernel timing).  The key-side kernel
- * reads the delta vector that the query-side kernel of an earlier call left in the workspace. */
+/* spion_attn_bwd only: run one of its two phases (for per-phase timing).  The key-side phase reads
+ * what the query-side phase of an earlier call with the same arguments and workspace left there
+ * (delta, the row statistics in log2 units, the key-side work list). */
 #define SPION_ATTN_BWD_QUERY_SIDE_ONLY 2u /* delta and dQ only */
 #define SPION_ATTN_BWD_KEY_SIDE_ONLY 4u   /* dK and dV only */
 

@@ -422,6 +422,29 @@ def test_attention_backward_is_deterministic(sp):
             assert torch.equal(a, b)
 
 
+def test_backward_phases_run_separately_give_the_same_bits(sp):
+    # the two phase flags (used for per-phase timing): query side, then key side on the same
+    # workspace, against the one-call backward
+    w = si.workload(2)
+    Q, K, V, dO = si.make_qkv_do(w, bh_limit=8)
+    A = si.make_score_map(w, Q, K)
+    pat = sp.generate_pattern(_dev(A), w.block, w.filt, w.thresh_mode, w.thresh_value)
+    q, k, v, do = [_dev(t, torch.bfloat16).view(2, 4, w.L, w.d) for t in (Q, K, V, dO)]
+    O, LSE = sp.attn_fwd(q, k, v, pat)
+    ref = sp.attn_bwd(q, k, v, O, do, LSE, pat)
+    code = sp.SPION_BF16
+    ws = torch.empty(sp.spion_attn_workspace_bytes(2, 4, w.L, w.d, w.block, code, pat.nnzb, True),
+                     dtype=torch.uint8, device="cuda")
+    got = [torch.full_like(q, float("nan")) for _ in range(3)]
+    for flags in (sp.SPION_ATTN_BWD_QUERY_SIDE_ONLY, sp.SPION_ATTN_BWD_KEY_SIDE_ONLY):
+        sp.spion_attn_bwd(q, k, v, O, do, LSE, got[0], got[1], got[2], pat.row_ptr, pat.col_idx,
+                          pat.col_ptr, pat.row_idx, pat.bsr_pos, pat.nnzb, 2, 4, w.L, w.d, w.block, code,
+                          flags=flags, workspace=ws)
+    torch.cuda.synchronize()
+    for g, r in zip(got, ref):
+        assert torch.equal(g, r)
+
+
 def test_error_codes_need_no_launch(sp):
     A = torch.zeros((64, 64), device="cuda")
     with pytest.raises(sp.SpionError) as e:
