@@ -118,6 +118,26 @@ __device__ __forceinline__ void mma_over_rows_swz(f32x4 (&acc)[4], const bf16_t*
     }
 }
 
+// Write this wave's 16 owned rows x 64 columns (accumulators in the transposed layout: lane (r, g)
+// holds columns 16 dt + 4 g .. + 3 of row r) as whole 128-byte rows, 16 bytes per lane, instead of
+// 8-byte pieces: through a 2 KB LDS patch private to the wave, 16-byte chunks permuted by the row.
+// LDS instructions of one wave execute in order, so no barrier is needed between the two halves.
+__device__ __forceinline__ void store_rows_coalesced(bf16_t* patch, bf16_t* __restrict__ grow0,
+                                                     const f32x4 (&acc)[4], float mul, int lane) {
+    const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        const int chunk = (dt * 2 + (g >> 1)) ^ (r & 7);
+        *reinterpret_cast<bf16x4*>(patch + r * kD + chunk * 8 + (g & 1) * 4) = to_quad<bf16_t>(acc[dt] * mul);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row = (lane >> 3) + 8 * j, c = lane & 7;
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(patch + row * kD + ((c ^ (row & 7)) << 3));
+        *reinterpret_cast<bf16x8*>(grow0 + (size_t)row * kD + c * 8) = v;
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // forward and backward query side: K / V tiles in two LDS stages, the next block loading while the
 // current one is multiplied.  Two stages of {K, V} are 32 KB at block 64; four workgroups share a CU
@@ -303,10 +323,11 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
         for (int dt = 0; dt < 4; ++dt) oacc[dt] *= a;
     }
     const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-    bf16_t* orow = O + head + (size_t)qrow * kD;
     SPION_TP(14);
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) store_quad<bf16_t>(orow + dt * 16 + 4 * g, oacc[dt] * inv);
+    // the stage that the last block did not use is free: every wave is past the barrier that followed
+    // its last reader, and the only load that ever targets this wave's 2 KB of it was the wave's own
+    bf16_t* patch = ((n & 1) ? sm1.k : sm0.k) + wave * (16 * kD);
+    store_rows_coalesced(patch, O + head + (size_t)(I * BS + wave * 16) * kD, oacc, inv, lane);
     if (g == 0) LSE[(size_t)bh * L + qrow] = lsum > 0.f ? (m + log2f(lsum)) * kLn2 : -INFINITY;
     SPION_TP(15);
 }
@@ -418,9 +439,9 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dq_bf16_kernel(
     }
     // an empty row never waited for its early load: it must land before this workgroup's LDS is freed
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
-    bf16_t* drow = dQ + head + (size_t)qrow * kD;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) store_quad<bf16_t>(drow + dt * 16 + 4 * g, dq[dt] * scale);
+    // through the stage the last block did not use (see the forward kernel)
+    bf16_t* patch = ((n & 1) ? sm1.k : sm0.k) + wave * (16 * kD);
+    store_rows_coalesced(patch, dQ + head + (size_t)(I * BS + wave * 16) * kD, dq, scale, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -562,13 +583,12 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_dkv_bf16_kernel(
 
     SPION_TP(14);
     if (slot < 0) {
-        bf16_t* dkrow = dK + head + (size_t)krow * kD;
-        bf16_t* dvrow = dV + head + (size_t)krow * kD;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-            store_quad<bf16_t>(dkrow + dt * 16 + 4 * g, dk[dt] * scale);
-            store_quad<bf16_t>(dvrow + dt * 16 + 4 * g, dv[dt]);
-        }
+        // stage n % 3 is free: its last reader was block n - 3, no load targets it any more, and the
+        // only loads that ever touched this wave's 2 KB of its Q and dO tiles were the wave's own
+        DkvSmem<BS>& fs = n % 3 == 0 ? sm0 : (n % 3 == 1 ? sm1 : sm2);
+        const size_t row0 = head + (size_t)(J * BS + wave * 16) * kD;
+        store_rows_coalesced(fs.q + wave * (16 * kD), dK + row0, dk, scale, lane);
+        store_rows_coalesced(fs.d + wave * (16 * kD), dV + row0, dv, 1.f, lane);
     } else {
         // fp32 partial tile of this chunk, unscaled: [head][slot][dK | dV][bs][64]
         float* pk = partial + ((size_t)bh * n_slots + slot) * (2 * BS * kD) + (size_t)(wave * 16 + r) * kD;
