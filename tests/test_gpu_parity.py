@@ -96,6 +96,20 @@ def test_pattern_large_block_grid_uses_the_workspace_path(sp):
     _check_pattern(sp, A, block, 1, si.T_MEAN_KSTD, 2.0)
 
 
+def test_pattern_at_the_largest_block_grid(sp):
+    # nb = 1024, the largest grid the library accepts: 2047 fill levels, one thread per block row
+    L, block = 16384, 16
+    rng = np.random.default_rng(5)
+    A = rng.random((L, L), dtype=np.float32)
+    for _ in range(3):
+        np.multiply(A, A, out=A)                  # x^8: a few large scores on a faint background
+    A[:, 5000:5016] += 0.5
+    i = np.arange(L)
+    A[i, i] += 0.4
+    np.minimum(A, 1.0, out=A)
+    _check_pattern(sp, A, block, 3, si.T_QUANTILE, 0.995)
+
+
 def test_pattern_plateau_map_and_tiny_values(sp):
     L, block = 128, 16
     A = np.zeros((L, L), dtype=np.float32)        # every pooled value equal: all ties
@@ -290,6 +304,87 @@ def test_attention_long_rows_find_their_diagonal(sp):
     fl[68, 68] = 0                                           # 71 entries, none of them the diagonal
     fl[5, :] = 1                                             # diagonal entry at position 5
     _run_attention_case(sp, Q, K, V, dO, fl, block, "bf16")
+
+
+@pytest.mark.parametrize("dtype,block", [("bf16", 32), ("f32", 16)])
+def test_attention_at_the_largest_block_grid(sp, dtype, block):
+    """nb = 1024 (L = 32768 at block 32, 16384 at block 16): a key block kept by every block row (103 key-side chunks),
+    a 120-row column, a 200-block row and a row without its diagonal block.  The dense oracle is out
+    of reach at this size, so the check is on sampled outputs: the oracle gives the probabilities of
+    one row at a time; O, LSE and dQ of sampled rows and dK, dV of sampled keys follow from them
+    with the gradient formulas of Eq. 5.  dO is zero except on two rows of every block row (and the
+    sampled rows): a row with dO = 0 adds nothing to dK, dV, so only those rows need the oracle,
+    while every chunk of every split column still carries a non-zero share."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    nb, d, BH, bh = 1024, 64, 2, 1
+    L = nb * block
+    scale = 1.0 / np.sqrt(d)
+    rng = np.random.default_rng(77)
+    fl = np.zeros((nb, nb), dtype=np.uint8)
+    I = np.arange(nb)
+    fl[I, I] = 1
+    fl[I[1:], I[:-1]] = 1
+    fl[I[:-1], I[1:]] = 1
+    fl[:, 700] = 1
+    fl[300:420, 77] = 1
+    fl[513, rng.choice(nb, 200, replace=False)] = 1
+    fl[900, 900] = 0
+    Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), dtype)
+                   for _ in range(4)]
+    rows = sorted({0, block - 1, block, 513 * block + 5, 514 * block - 1, 900 * block + 3, 77 * block, L - 1}
+                  | set(rng.integers(0, L, 16).tolist()))
+    live = sorted(set(rows) | set((I * block + I % block).tolist())
+                  | set((I * block + (7 * I + 3) % block).tolist()))       # rows with dO != 0
+    dead = np.ones(L, dtype=bool)
+    dead[live] = False
+    dO[:, dead, :] = 0.0
+    pat = _pattern_from_mask(sp, fl, block)
+    q, k, v, do = [_dev(t, _torch_dtype(dtype)).view(1, BH, L, d) for t in (Q, K, V, dO)]
+    O, LSE = sp.attn_fwd(q, k, v, pat)
+    dQ, dK, dV = sp.attn_bwd(q, k, v, O, do, LSE, pat)
+    torch.cuda.synchronize()
+    got = {n: t.float().cpu().numpy().reshape(BH, L, d)[bh] for n, t in
+           (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV))}
+    lse = LSE.cpu().numpy().reshape(BH, L)[bh]
+    for x in got.values():
+        assert np.all(np.isfinite(x))
+
+    assert not got["dQ"][dead].any()                                   # dO = 0 rows: dS = 0 exactly
+    P = np.repeat(np.repeat(fl, block, axis=0), block, axis=1)         # the mask, element by element
+    Q64, K64, V64, dO64 = [np.ascontiguousarray(t, dtype=np.float64) for t in (Q, K, V, dO)]
+    keys = np.array([700 * block + 1, 701 * block - 2, 77 * block + 7, 77 * block + block // 2, 5, L - 2])
+    Vk, n_keys = V64[bh][keys], len(keys)
+
+    def one_row(i):
+        p = oracle.attn_probs_row(Q64, K64, P, bh, i)
+        o = p @ V64[bh]
+        delta = dO64[bh, i] @ o
+        ds_k = p[keys] * (Vk @ dO64[bh, i] - delta)
+        out = [np.outer(p[keys], dO64[bh, i]), scale * np.outer(ds_k, Q64[bh, i])]
+        if i in rows:
+            ds = p * (V64[bh] @ dO64[bh, i] - delta)
+            j = int(np.argmax(p))
+            out += [o, scale * (ds @ K64[bh]), scale * (Q64[bh, i] @ K64[bh, j]) - np.log(p[j])]
+        return out
+
+    rdV, rdK = np.zeros((n_keys, d)), np.zeros((n_keys, d))
+    rO, rdQ, rLSE = {}, {}, {}
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        for i, out in zip(live, pool.map(one_row, live, chunksize=16)):
+            rdV += out[0]
+            rdK += out[1]
+            if len(out) > 2:
+                rO[i], rdQ[i], rLSE[i] = out[2], out[3], out[4]
+    tol = TOL[dtype]
+    checks = {"O": (got["O"][rows], np.stack([rO[i] for i in rows])),
+              "dQ": (got["dQ"][rows], np.stack([rdQ[i] for i in rows])),
+              "dK": (got["dK"][keys], rdK), "dV": (got["dV"][keys], rdV)}
+    for name, (x, ref) in checks.items():
+        fro, mx = _rel_errors(x, ref)
+        assert fro <= tol and mx <= tol, (name, fro, mx)
+    ref_lse = np.array([rLSE[i] for i in rows])
+    assert np.abs(lse[rows] - ref_lse).max() <= tol * max(np.abs(ref_lse).max(), 1.0)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
