@@ -116,3 +116,21 @@ def test_useful_flop_and_byte_accounting():
     t = 16 * 4096 * 64 * 2
     assert acc.algorithmic_bytes("path", 16, 4096, 64, 2) == 12 * t + 2 * 16 * 4096 * 4
     assert acc.algorithmic_bytes("fwd", 16, 4096, 64, 2) == 4 * t + 16 * 4096 * 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "single-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_product_package_does_not_import_the_oracle():
+    # the oracle is test infrastructure: nothing under the package may reach it
+    pkg = os.path.join(ROOT, "paper_2309_12578_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            text = open(os.path.join(pkg, name)).read()
+            assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), name
