@@ -22,7 +22,9 @@
  *     host before anything is enqueued; nothing is written in that case.
  *   - Tensors Q, K, V, O, dO, dQ, dK, dV are [B, H, L, d] contiguous (d fastest) in the element type
  *     named by `dtype`; LSE is fp32 [B, H, L].  Supported: d == 64, block in {16, 32, 64},
- *     L % block == 0, L / block <= SPION_MAX_NB.
+ *     L % block == 0, L / block <= SPION_MAX_NB, and B * H * (L / block) < 2^31 (one workgroup per
+ *     block row and head; the backward also needs B * H * (nnzb / 10 + L / block) < 2^31).  A shape
+ *     outside these limits is SPION_ERR_SHAPE.
  *   - One pattern (one BSR/BSC index) is shared by all batch items and heads of a layer.
  */
 #ifndef SPION_H_

@@ -321,6 +321,12 @@ size_t attn_bwd_workspace_bytes(int BH, int L, int bs, int nb, int nnzb) {
     return ws.total;
 }
 
+bool attn_bwd_grids_fit(int BH, int L, int bs, int nb, int nnzb) {
+    const BwdWorkspace ws(BH, L, bs, nb, nnzb);
+    const int64_t limit = 0x7fffffffll;
+    return (int64_t)ws.w_max * BH <= limit && (int64_t)ws.split_max * BH * (bs / 16) <= limit;
+}
+
 BwdWorkspace::BwdWorkspace(int BH, int L, int bs, int nb, int nnzb) {
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     w_max = key_work_items_max(nnzb, nb);

@@ -201,6 +201,7 @@ int spion_attn_bwd(const void* Q, const void* K, const void* V, const void* O, c
         return SPION_ERR_NULL;
     const int rc = attn_params_ok(p, nnzb);
     if (rc != SPION_OK) return rc;
+    if (!spion::attn_bwd_grids_fit(p->B * p->H, p->L, p->block, p->L / p->block, nnzb)) return SPION_ERR_SHAPE;
     const size_t need = spion_attn_workspace_bytes(p, nnzb, 1);
     if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need)
         return SPION_ERR_WORKSPACE;

@@ -44,6 +44,8 @@ struct BwdWorkspace {
     BwdWorkspace(int BH, int L, int bs, int nb, int nnzb);
 };
 size_t attn_bwd_workspace_bytes(int BH, int L, int bs, int nb, int nnzb);
+// false when a backward launch for this shape would need more workgroups than a 1-D grid can hold
+bool attn_bwd_grids_fit(int BH, int L, int bs, int nb, int nnzb);
 
 // attn_bf16_kernels.hip: tuned bf16 kernels, BS in {32, 64}
 template <int BS>

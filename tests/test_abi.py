@@ -89,6 +89,12 @@ def test_argument_errors_are_reported_before_any_launch():
     b2 = list(bargs)
     b2[15] = ctypes.byref(both)
     assert lib.spion_attn_bwd(*b2) == -5                                    # both "only" flags at once
+    # forward grid fits (B H nb < 2^31) but the key side of the backward would need more workgroups
+    huge = _AttnParams(1 << 10, 1 << 10, 16384, 64, 16, sp.SPION_BF16, 0.0, 0)
+    b3 = list(bargs)
+    b3[14] = 1024 * 1024
+    b3[15] = ctypes.byref(huge)
+    assert lib.spion_attn_bwd(*b3) == -2
 
 
 def test_binding_refuses_cpu_tensors():
