@@ -46,6 +46,7 @@ typedef enum {
     SPION_ERR_DTYPE = -3,     /* dtype is not SPION_F32 / SPION_BF16 */
     SPION_ERR_WORKSPACE = -4, /* workspace missing, misaligned (256 B) or too small */
     SPION_ERR_PARAM = -5,     /* even filter, filter too large, quantile outside [0,1], bad flags */
+    SPION_ERR_INDEX = -6,     /* malformed block-sparse index (written by spion_index_check only) */
     SPION_ERR_HIP = -7        /* a HIP runtime call failed (launch error) */
 } spion_status;
 
@@ -95,6 +96,20 @@ int spion_pattern(const float *A_s, const spion_pattern_params *p, uint8_t *fl_o
                   int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx, int32_t *bsr_pos,
                   int32_t *nnzb, int64_t *pool_sum, void *workspace, size_t workspace_bytes,
                   void *hip_stream);
+
+/*
+ * Checks a block-sparse index (the compressed form of the pattern, Section 4.3) before it is handed
+ * to spion_attn_fwd / spion_attn_bwd, which trust it: an index produced by spion_pattern is always
+ * well formed, one built elsewhere may not be, and an entry out of range would be an out-of-bounds
+ * access there.  Writes SPION_OK or SPION_ERR_INDEX to the device int32 `status` (read it back after
+ * the stream has reached this point).  Checked: row_ptr runs from 0 to nnzb without decreasing; the
+ * block columns of every row lie in [0, nb) and ascend strictly; and, when the transposed index is
+ * given (col_ptr, row_idx, bsr_pos: all three or none), the same for it, plus bsr_pos[k] naming the
+ * position in col_idx of the very block (row_idx[k], column of k).  nb = L / block, nb <= SPION_MAX_NB.
+ */
+int spion_index_check(const int32_t *row_ptr, const int32_t *col_idx, const int32_t *col_ptr,
+                      const int32_t *row_idx, const int32_t *bsr_pos, int32_t nb, int32_t nnzb,
+                      int32_t *status, void *hip_stream);
 
 /* spion_attn_params.flags */
 #define SPION_ATTN_PAPER_DENOM 1u /* add Algorithm 6's exp(-max) * (L - kept) term to the row sum */

@@ -12,7 +12,7 @@ from .binding import (  # noqa: F401
     spion_pattern_workspace_bytes, spion_pattern, spion_attn_workspace_bytes,
     spion_attn_fwd, spion_attn_bwd, generate_pattern, attn_fwd, attn_bwd,
     spion_score_mean, spion_frobenius_workspace_bytes, spion_frobenius_distance, score_mean,
-    frobenius_distance,
+    frobenius_distance, spion_index_check, index_is_well_formed,
 )
 from .autograd import sparse_attention  # noqa: E402,F401
 from .sublayer import SparseMHA  # noqa: E402,F401

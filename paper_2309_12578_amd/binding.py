@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.spion_pattern_workspace_bytes.argtypes = [i32, i32]
     lib.spion_pattern.restype = ctypes.c_int
     lib.spion_pattern.argtypes = [vp, ctypes.POINTER(_PatternParams)] + [vp] * 8 + [vp, sz, vp]
+    lib.spion_index_check.restype = ctypes.c_int
+    lib.spion_index_check.argtypes = [vp] * 5 + [i32, i32, vp, vp]
     lib.spion_score_mean.restype = ctypes.c_int
     lib.spion_score_mean.argtypes = [vp, i32, i32, i32, vp, vp]
     lib.spion_frobenius_workspace_bytes.restype = sz
@@ -128,6 +130,14 @@ def spion_pattern(A_s, L, block, filt, thresh_mode, thresh_value, fl_out, row_pt
                               _ptr(workspace), ws_bytes, _stream(stream))
     if rc != 0:
         raise SpionError(rc, "spion_pattern")
+
+
+def spion_index_check(row_ptr, col_idx, col_ptr, row_idx, bsr_pos, nb: int, nnzb: int, status,
+                      stream=None) -> None:
+    rc = load().spion_index_check(_ptr(row_ptr), _ptr(col_idx), _ptr(col_ptr), _ptr(row_idx), _ptr(bsr_pos),
+                                  int(nb), int(nnzb), _ptr(status), _stream(stream))
+    if rc != 0:
+        raise SpionError(rc, "spion_index_check")
 
 
 def spion_score_mean(A_maps, n_maps: int, L: int, dtype: int, A_s, stream=None) -> None:
@@ -227,6 +237,14 @@ def generate_pattern(A_s: torch.Tensor, block: int, filt: int, thresh_mode: int,
     if sync:
         out.nnzb = int(out.nnzb_dev.item())
     return out
+
+
+def index_is_well_formed(pat: Pattern) -> bool:
+    """Runs spion_index_check on a pattern's index (synchronises to read the verdict back)."""
+    status = torch.empty(1, dtype=torch.int32, device=pat.row_ptr.device)
+    spion_index_check(pat.row_ptr, pat.col_idx, pat.col_ptr, pat.row_idx, pat.bsr_pos, pat.nb, pat.nnzb,
+                      status)
+    return int(status.item()) == 0
 
 
 def score_mean(A_maps: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

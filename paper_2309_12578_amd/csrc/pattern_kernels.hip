@@ -542,6 +542,73 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
+// index check (one workgroup)
+// ------------------------------------------------------------------------------------------------
+// The attention kernels trust their index: an entry out of range there is an access out of bounds.
+// An index that did not come from pattern_finish_kernel can be checked here first.  Three stages,
+// each reading only what the stage before has shown to be in range: (1) the pointer arrays run
+// from 0 to nnzb without decreasing; (2) the entries of every row (column) lie in [0, nb) and
+// ascend strictly; (3) every entry of the transposed index names a position of the row-wise index
+// that lies in the row it claims and holds the column it claims (with equal counts and distinct
+// (row, column) pairs, that makes the transposed index the exact transpose).
+__global__ __launch_bounds__(1024) void index_check_kernel(
+    const int* __restrict__ row_ptr, const int* __restrict__ col_idx, const int* __restrict__ col_ptr,
+    const int* __restrict__ row_idx, const int* __restrict__ bsr_pos, int nb, int nnzb, int err_code,
+    int* __restrict__ status) {
+    __shared__ int bad;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
+    if (tid == 0) bad = 0;
+    __syncthreads();
+    auto pointers_ok = [&](const int* ptr) {
+        bool ok = true;
+        for (int i = tid; i < nb; i += blockDim.x) {
+            const int a = ptr[i], b = ptr[i + 1];
+            ok = ok && a >= 0 && b >= a && b <= nnzb;
+        }
+        if (tid == 0) ok = ok && ptr[0] == 0 && ptr[nb] == nnzb;
+        return ok;
+    };
+    if (!pointers_ok(row_ptr)) bad = 1;
+    if (col_ptr && !pointers_ok(col_ptr)) bad = 1;
+    __syncthreads();
+    if (bad) {
+        if (tid == 0) *status = err_code;
+        return;
+    }
+    auto entries_ok = [&](const int* ptr, const int* idx) {
+        bool ok = true;
+        for (int i = wave; i < nb; i += n_waves) {
+            const int a = ptr[i], b = ptr[i + 1];
+            for (int k = a + lane; k < b; k += 64) {
+                const int c = idx[k];
+                ok = ok && c >= 0 && c < nb && (k == a || idx[k - 1] < c);
+            }
+        }
+        return ok;
+    };
+    if (!entries_ok(row_ptr, col_idx)) bad = 1;
+    if (col_ptr && !entries_ok(col_ptr, row_idx)) bad = 1;
+    __syncthreads();
+    if (bad) {
+        if (tid == 0) *status = err_code;
+        return;
+    }
+    if (col_ptr) {
+        bool ok = true;
+        for (int j = wave; j < nb; j += n_waves) {
+            const int a = col_ptr[j], b = col_ptr[j + 1];
+            for (int k = a + lane; k < b; k += 64) {
+                const int i = row_idx[k], pos = bsr_pos[k];
+                ok = ok && pos >= row_ptr[i] && pos < row_ptr[i + 1] && col_idx[pos] == j;
+            }
+        }
+        if (!ok) bad = 1;
+    }
+    __syncthreads();
+    if (tid == 0) *status = bad ? err_code : 0;
+}
+
+// ------------------------------------------------------------------------------------------------
 // host launchers
 // ------------------------------------------------------------------------------------------------
 hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* pool, hipStream_t st) {
@@ -571,6 +638,13 @@ hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long l
     pattern_finish_kernel<<<dim3(1), dim3(kFinishThreads), dyn, st>>>(
         pool, nb, mode, k_rank, kval, t_abs, no_fill, use_lds, mask, expd, pos, fl, row_ptr, col_idx,
         col_ptr, row_idx, bsr_pos, nnzb);
+    return hipGetLastError();
+}
+
+hipError_t launch_index_check(const int* row_ptr, const int* col_idx, const int* col_ptr, const int* row_idx,
+                              const int* bsr_pos, int nb, int nnzb, int err_code, int* status, hipStream_t st) {
+    index_check_kernel<<<dim3(1), dim3(1024), 0, st>>>(row_ptr, col_idx, col_ptr, row_idx, bsr_pos, nb, nnzb,
+                                                       err_code, status);
     return hipGetLastError();
 }
 

@@ -74,6 +74,7 @@ const char* spion_strerror(int status) {
         case SPION_ERR_DTYPE: return "unsupported dtype";
         case SPION_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case SPION_ERR_PARAM: return "invalid parameter value";
+        case SPION_ERR_INDEX: return "malformed block-sparse index";
         case SPION_ERR_HIP: return "HIP runtime error";
         default: return "unknown status";
     }
@@ -173,6 +174,19 @@ size_t spion_attn_workspace_bytes(const spion_attn_params* p, int32_t nnzb, int3
     if (!p || attn_params_ok(p, nnzb) != SPION_OK) return (size_t)-1;
     if (!is_bwd) return 0;
     return spion::attn_bwd_workspace_bytes(p->B * p->H, p->L, p->block, p->L / p->block, nnzb);
+}
+
+int spion_index_check(const int32_t* row_ptr, const int32_t* col_idx, const int32_t* col_ptr,
+                      const int32_t* row_idx, const int32_t* bsr_pos, int32_t nb, int32_t nnzb,
+                      int32_t* status, void* hip_stream) {
+    if (!row_ptr || !col_idx || !status) return SPION_ERR_NULL;
+    const bool any_bsc = col_ptr || row_idx || bsr_pos;
+    if (any_bsc && !(col_ptr && row_idx && bsr_pos)) return SPION_ERR_NULL;
+    if (nb <= 0 || nb > SPION_MAX_NB || nnzb < 0 || (int64_t)nnzb > (int64_t)nb * nb) return SPION_ERR_SHAPE;
+    if (spion::launch_index_check(row_ptr, col_idx, col_ptr, row_idx, bsr_pos, nb, nnzb, SPION_ERR_INDEX,
+                                  status, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return SPION_ERR_HIP;
+    return SPION_OK;
 }
 
 int spion_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,

@@ -15,6 +15,8 @@ hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long l
                                  int* bsr_pos, int* nnzb, hipStream_t st);
 
 // producer_kernels.hip
+hipError_t launch_index_check(const int* row_ptr, const int* col_idx, const int* col_ptr, const int* row_idx,
+                              const int* bsr_pos, int nb, int nnzb, int err_code, int* status, hipStream_t st);
 hipError_t launch_score_mean(const void* A, int is_bf16, int n_maps, size_t n, float* out, hipStream_t st);
 size_t frobenius_workspace_bytes();
 hipError_t launch_frobenius_distance(const float* a, const float* b, size_t n, double* out, void* workspace,

@@ -89,6 +89,11 @@ def test_argument_errors_are_reported_before_any_launch():
     b2 = list(bargs)
     b2[15] = ctypes.byref(both)
     assert lib.spion_attn_bwd(*b2) == -5                                    # both "only" flags at once
+    status = ctypes.c_void_p(512)
+    assert lib.spion_index_check(fake, fake, none, none, none, 16, 19, none, none) == -1      # no status
+    assert lib.spion_index_check(fake, fake, fake, none, none, 16, 19, status, none) == -1    # partial BSC
+    assert lib.spion_index_check(fake, fake, none, none, none, 2000, 19, status, none) == -2  # nb too large
+    assert lib.spion_index_check(fake, fake, none, none, none, 16, 257, status, none) == -2   # nnzb > nb^2
     # forward grid fits (B H nb < 2^31) but the key side of the backward would need more workgroups
     huge = _AttnParams(1 << 10, 1 << 10, 16384, 64, 16, sp.SPION_BF16, 0.0, 0)
     b3 = list(bargs)

@@ -540,6 +540,54 @@ def test_backward_phases_run_separately_give_the_same_bits(sp):
         assert torch.equal(g, r)
 
 
+def test_index_check_accepts_generated_patterns_and_flags_malformed_ones(sp):
+    """spion_index_check against the oracle's compaction: the oracle's index of a random mask passes;
+    each single corruption of it (every one still safe to read: the checker looks at an entry only
+    after the stage before has shown its position to be in range) is reported."""
+    w = si.workload(2)
+    Q, K, _, _ = si.make_qkv_do(w, bh_limit=4)
+    pat = sp.generate_pattern(_dev(si.make_score_map(w, Q, K)), w.block, w.filt, w.thresh_mode, w.thresh_value)
+    assert sp.index_is_well_formed(pat)
+
+    nb = 40
+    fl = si.random_block_mask(nb, 0.3, seed=9)
+    good = _pattern_from_mask(sp, fl, 16)
+    assert sp.index_is_well_formed(good)
+    bsr_only = _pattern_from_mask(sp, fl, 16)
+    bsr_only.col_ptr = bsr_only.row_idx = bsr_only.bsr_pos = None
+    assert sp.index_is_well_formed(bsr_only)
+    empty = _pattern_from_mask(sp, np.zeros((nb, nb), dtype=np.uint8), 16)
+    assert sp.index_is_well_formed(empty)
+
+    c = oracle.compact(fl)
+    n = c["nnzb"]
+    r5 = int(c["row_ptr"][5])
+    assert c["row_ptr"][6] - r5 >= 2 and c["col_ptr"][4] - c["col_ptr"][3] >= 2
+
+    def corrupt(field, index, value):
+        bad = _pattern_from_mask(sp, fl, 16)
+        getattr(bad, field)[index] = value
+        return bad
+
+    cases = {
+        "row_ptr decreases": corrupt("row_ptr", 7, int(c["row_ptr"][6]) - 1),
+        "row_ptr does not start at 0": corrupt("row_ptr", 0, 1),
+        "row_ptr beyond nnzb": corrupt("row_ptr", nb, n + 3),
+        "column out of range": corrupt("col_idx", r5, nb),
+        "negative column": corrupt("col_idx", r5, -1),
+        "columns not ascending": corrupt("col_idx", r5 + 1, int(c["col_idx"][r5])),
+        "col_ptr decreases": corrupt("col_ptr", 3, int(c["col_ptr"][4]) + 1),
+        "row out of range": corrupt("row_idx", int(c["col_ptr"][3]), nb + 5),
+        "bsr_pos out of range": corrupt("bsr_pos", 0, n),
+        "bsr_pos names another block": corrupt("bsr_pos", int(c["col_ptr"][3]), int(c["bsr_pos"][c["col_ptr"][3] + 1])),
+    }
+    for what, bad in cases.items():
+        assert not sp.index_is_well_formed(bad), what
+    wrong_count = _pattern_from_mask(sp, fl, 16)
+    wrong_count.nnzb = n - 1
+    assert not sp.index_is_well_formed(wrong_count)
+
+
 def test_error_codes_need_no_launch(sp):
     A = torch.zeros((64, 64), device="cuda")
     with pytest.raises(sp.SpionError) as e:
