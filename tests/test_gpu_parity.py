@@ -588,6 +588,85 @@ def test_index_check_accepts_generated_patterns_and_flags_malformed_ones(sp):
     assert not sp.index_is_well_formed(wrong_count)
 
 
+def test_step_and_pattern_replay_from_hip_graphs(sp):
+    """The library enqueues kernels only (no allocation, no memset, no synchronisation), so a
+    forward + backward step and a pattern generation can be captured into HIP graphs.  Every replay,
+    with eager work and synchronisations in between and with new contents in the captured buffers,
+    must give the bits of the eager calls."""
+    w = si.workload(2)
+    B, H = 2, 4
+    code = sp.SPION_BF16
+    sets = []
+    for off in (0, 1):
+        Q, K, V, dO = si.make_qkv_do(w, seed_offset=off, bh_limit=B * H)
+        sets.append([_dev(t, torch.bfloat16).view(B, H, w.L, w.d) for t in (Q, K, V, dO)])
+    A = [_dev(si.make_score_map(w, Q, K, seed_offset=off)) for off in (0, 1)]
+    pat = sp.generate_pattern(A[0], w.block, w.filt, w.thresh_mode, w.thresh_value)
+    nnzb = pat.nnzb
+
+    def eager(qkvdo):
+        O, LSE = sp.attn_fwd(*qkvdo[:3], pat)
+        return [O, LSE] + list(sp.attn_bwd(*qkvdo[:3], O, qkvdo[3], LSE, pat))
+
+    want = [[t.clone() for t in eager(s_)] for s_ in sets]
+    want_pat = []
+    for a in A:
+        p_ = sp.generate_pattern(a, w.block, w.filt, w.thresh_mode, w.thresh_value)
+        want_pat.append((p_.fl_out.clone(), p_.col_idx[:p_.nnzb].clone(), p_.nnzb))
+
+    # static buffers of the captured step
+    q, k, v, do = [torch.empty_like(t) for t in sets[0]]
+    O, dQ, dK, dV = [torch.empty_like(q) for _ in range(4)]
+    LSE = torch.empty((B, H, w.L), dtype=torch.float32, device="cuda")
+    ws = torch.empty(sp.spion_attn_workspace_bytes(B, H, w.L, w.d, w.block, code, nnzb, True),
+                     dtype=torch.uint8, device="cuda")
+    a_static = torch.empty_like(A[0])
+    pat_static = sp.generate_pattern(A[0], w.block, w.filt, w.thresh_mode, w.thresh_value)
+    ws_pat = torch.empty(sp.spion_pattern_workspace_bytes(w.L, w.block), dtype=torch.uint8, device="cuda")
+
+    def step():
+        sp.spion_attn_fwd(q, k, v, O, LSE, pat.row_ptr, pat.col_idx, nnzb, B, H, w.L, w.d, w.block, code)
+        sp.spion_attn_bwd(q, k, v, O, do, LSE, dQ, dK, dV, pat.row_ptr, pat.col_idx, pat.col_ptr,
+                          pat.row_idx, pat.bsr_pos, nnzb, B, H, w.L, w.d, w.block, code, workspace=ws)
+
+    def regen():
+        sp.generate_pattern(a_static, w.block, w.filt, w.thresh_mode, w.thresh_value, sync=False,
+                            out=pat_static, workspace=ws_pat)
+
+    for t, src in zip((q, k, v, do), sets[0]):
+        t.copy_(src)
+    a_static.copy_(A[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+        regen()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g_step, g_pat = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_step):
+        step()
+    with torch.cuda.graph(g_pat):
+        regen()
+
+    for which in (0, 1, 0, 1, 1):
+        for t, src in zip((q, k, v, do), sets[which]):
+            t.copy_(src)
+        a_static.copy_(A[which])
+        for t in (O, dQ, dK, dV, LSE):
+            t.fill_(float("nan"))
+        g_step.replay()
+        g_pat.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((O, LSE, dQ, dK, dV), want[which]):
+            assert torch.equal(got, ref)
+        fl_ref, col_ref, n_ref = want_pat[which]
+        assert int(pat_static.nnzb_dev.item()) == n_ref
+        assert torch.equal(pat_static.fl_out, fl_ref) and torch.equal(pat_static.col_idx[:n_ref], col_ref)
+        eager(sets[1 - which])                      # the program's own eager work between replays
+        torch.cuda.synchronize()
+
+
 def test_error_codes_need_no_launch(sp):
     A = torch.zeros((64, 64), device="cuda")
     with pytest.raises(sp.SpionError) as e:
