@@ -277,23 +277,27 @@ def main() -> int:
     run(args.warmup, False)
     ms_warm = timed(args.steps, False)
 
-    # ---------------------------------------------------------------- per-kernel durations (HIP events on
-    # the launch stream, which is torch's current stream), per layer
+    # ---------------------------------------------------------------- per-phase durations (HIP events on
+    # the launch stream, which is torch's current stream), per layer: K launches of one phase back to
+    # back on the rotating buffer sets between two events, so that the figure is the kernels' own
+    # duration (what a kernel trace shows) without the cost of an event pair per launch
     per_layer = []
+    phases = (lambda ly, s: fwd(ly, s),
+              lambda ly, s: bwd(ly, s, sp.SPION_ATTN_BWD_QUERY_SIDE_ONLY),
+              lambda ly, s: bwd(ly, s, sp.SPION_ATTN_BWD_KEY_SIDE_ONLY))
     for ly in prepared:
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-        torch.cuda.synchronize()
-        for i in range(args.steps):
-            s = ly.sets[i % n_sets]
-            evs[i][0].record()
-            fwd(ly, s)
-            evs[i][1].record()
-            bwd(ly, s, sp.SPION_ATTN_BWD_QUERY_SIDE_ONLY)
-            evs[i][2].record()
-            bwd(ly, s, sp.SPION_ATTN_BWD_KEY_SIDE_ONLY)
-            evs[i][3].record()
-        torch.cuda.synchronize()
-        km = {n: float(np.mean([e[j].elapsed_time(e[j + 1]) for e in evs])) for j, n in enumerate(KERNELS)}
+        km = {}
+        for name, phase in zip(KERNELS, phases):
+            for i in range(args.warmup):
+                phase(ly, ly.sets[i % n_sets])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(args.steps):
+                phase(ly, ly.sets[i % n_sets])
+            e1.record()
+            torch.cuda.synchronize()
+            km[name] = e0.elapsed_time(e1) / args.steps
         fl = acc.useful_flops(ly.nnzb, ly.w.block, ly.w.d, BH, products=6)
         tot = sum(km.values())
         per_layer.append({"layer": ly.w.layer, "nnzb": ly.nnzb, "block_density": round(ly.density, 5),
