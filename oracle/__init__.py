@@ -23,8 +23,6 @@ _LIB = os.path.join(_HERE, "libspion_oracle.so")
 T_ABS, T_QUANTILE, T_MEAN_KSTD = 0, 1, 2
 ATTN_PAPER_DENOM = 1
 
-ERR_BUDGET = -2
-
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
@@ -109,12 +107,12 @@ def make_thresh_double(td: float) -> _Thresh:
     return _Thresh(0, 0, 0, float(td))
 
 
-def fill(ps: np.ndarray, t: _Thresh, force_diag: bool = True, budget: int = 200_000_000) -> np.ndarray:
+def fill(ps: np.ndarray, t: _Thresh, force_diag: bool = True) -> np.ndarray:
     ps = np.ascontiguousarray(ps, dtype=np.int64)
     nb = ps.shape[0]
     out = np.empty((nb, nb), dtype=np.uint8)
     rc = lib().oracle_fill(_p(ps), ctypes.c_int32(nb), ctypes.byref(t), ctypes.c_int32(int(force_diag)),
-                           ctypes.c_int64(budget), _p(out))
+                           _p(out))
     _chk(rc, "fill")
     return out
 

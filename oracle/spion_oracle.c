@@ -38,7 +38,6 @@
 
 #define ORACLE_OK 0
 #define ORACLE_ERR_ARG -1
-#define ORACLE_ERR_BUDGET -2 /* recursion visited more cells than the caller's budget */
 #define ORACLE_ERR_NOMEM -3
 
 #define FIXED_POINT_SCALE 1099511627776.0 /* 2^40 */
@@ -173,54 +172,60 @@ static int above(int64_t x, const oracle_thresh *t) {
     return t->is_int ? (x > t->ti) : ((double)x > t->td);
 }
 
-typedef struct {
-    const int64_t *x;
-    uint8_t *fl;
-    int32_t nb;
-    const oracle_thresh *t;
-    int64_t calls, budget;
-} fill_ctx;
-
-/* Algorithm 4, as printed: stop on the last row or column; m = max of the lower, right and
- * lower-right neighbours; each neighbour (in that order) that equals m and is not yet marked is
- * marked if it exceeds t and is then expanded recursively whether or not it was marked. */
-static void flood_fill(fill_ctx *c, int32_t r, int32_t col) {
-    if (c->calls++ >= c->budget) return;
-    const int32_t nb = c->nb;
-    if (r + 1 == nb || col + 1 == nb) return;
-    const int64_t down = c->x[(int64_t)(r + 1) * nb + col];
-    const int64_t right = c->x[(int64_t)r * nb + col + 1];
-    const int64_t diag = c->x[(int64_t)(r + 1) * nb + col + 1];
-    int64_t m = down;
-    if (right > m) m = right;
-    if (diag > m) m = diag;
-    if (down == m && c->fl[(int64_t)(r + 1) * nb + col] == 0) {
-        if (above(down, c->t)) c->fl[(int64_t)(r + 1) * nb + col] = 1;
-        flood_fill(c, r + 1, col);
-    }
-    if (right == m && c->fl[(int64_t)r * nb + col + 1] == 0) {
-        if (above(right, c->t)) c->fl[(int64_t)r * nb + col + 1] = 1;
-        flood_fill(c, r, col + 1);
-    }
-    if (diag == m && c->fl[(int64_t)(r + 1) * nb + col + 1] == 0) {
-        if (above(diag, c->t)) c->fl[(int64_t)(r + 1) * nb + col + 1] = 1;
-        flood_fill(c, r + 1, col + 1);
-    }
-}
-
-/* Algorithm 3 from "initialize fl_out with zeros" to the forced diagonal: seeds (0,i) for every
- * column i, then (j,0) for every row j, then fl_out[k][k] = 1 (after the fill, as the algorithm
- * orders it; the prose mentions the diagonal earlier, the pseudo-code decides).
- * `budget` bounds the number of flood_fill calls (plateaus of equal sub-threshold values make
- * the literal recursion exponential); ORACLE_ERR_BUDGET is returned when it is exceeded. */
+/* Algorithm 4 driven the way Algorithm 3 drives it (zeroed fl_out; one walk from every cell of the
+ * first row, then one from every cell of the first column; the diagonal forced afterwards),
+ * restated as walks over an explicit stack.
+ *
+ * A walk that stands on cell (r, c) outside the last row and column looks at the cells below, to
+ * the right and below-right of it; those equal to the largest of the three are its successors
+ * (all of them when values tie).  A successor that is not marked yet is marked if it exceeds t,
+ * and the walk continues from it whether it was marked or not; an already marked successor ends
+ * that branch, and so does the last row or column.  A seed is not marked by its own walk.
+ *
+ * Moves never decrease r or c, so by the time a cell is met again everything reachable from it
+ * has been visited: walking from it a second time can mark nothing new.  `walked` records the
+ * cells a walk has continued from, each is expanded once, and the work is bounded by 3 nb^2
+ * steps (re-expanding unmarked cells, as a literal recursion would, is exponential on plateaus
+ * of equal sub-threshold values and gives the same fl_out). */
 int oracle_fill(const int64_t *pool_sum, int32_t nb, const oracle_thresh *t, int32_t force_diag,
-                int64_t budget, uint8_t *fl_out) {
+                uint8_t *fl_out) {
     if (!pool_sum || !t || !fl_out || nb <= 0) return ORACLE_ERR_ARG;
-    memset(fl_out, 0, (size_t)nb * nb);
-    fill_ctx c = {pool_sum, fl_out, nb, t, 0, budget > 0 ? budget : INT64_MAX};
-    for (int32_t i = 0; i < nb; ++i) flood_fill(&c, 0, i);
-    for (int32_t j = 0; j < nb; ++j) flood_fill(&c, j, 0);
-    if (c.calls > c.budget) return ORACLE_ERR_BUDGET;
+    const int64_t n = (int64_t)nb * nb;
+    uint8_t *walked = (uint8_t *)calloc((size_t)n, 1);
+    int64_t *stack = (int64_t *)malloc((size_t)(n + 2 * (int64_t)nb) * sizeof(int64_t));
+    if (!walked || !stack) {
+        free(walked);
+        free(stack);
+        return ORACLE_ERR_NOMEM;
+    }
+    memset(fl_out, 0, (size_t)n);
+    static const int32_t step_r[3] = {1, 0, 1}, step_c[3] = {0, 1, 1}; /* below, right, below-right */
+    for (int32_t s = 0; s < 2 * nb; ++s) {
+        /* seeds in Algorithm 3's order: (0, 0..nb-1), then (0..nb-1, 0) */
+        int64_t top = 0;
+        stack[top++] = s < nb ? (int64_t)s : (int64_t)(s - nb) * nb;
+        while (top > 0) {
+            const int64_t cell = stack[--top];
+            const int32_t r = (int32_t)(cell / nb), c = (int32_t)(cell % nb);
+            if (r == nb - 1 || c == nb - 1) continue;
+            int64_t best = INT64_MIN;
+            for (int k = 0; k < 3; ++k) {
+                const int64_t v = pool_sum[(int64_t)(r + step_r[k]) * nb + (c + step_c[k])];
+                if (v > best) best = v;
+            }
+            for (int k = 0; k < 3; ++k) {
+                const int64_t nxt = (int64_t)(r + step_r[k]) * nb + (c + step_c[k]);
+                if (pool_sum[nxt] != best || fl_out[nxt]) continue;
+                if (above(pool_sum[nxt], t)) fl_out[nxt] = 1;
+                if (!walked[nxt]) {
+                    walked[nxt] = 1;
+                    stack[top++] = nxt;
+                }
+            }
+        }
+    }
+    free(walked);
+    free(stack);
     if (force_diag)
         for (int32_t k = 0; k < nb; ++k) fl_out[(int64_t)k * nb + k] = 1;
     return ORACLE_OK;

@@ -157,8 +157,18 @@ def test_paper_denominator_flag():
     E = np.exp(S - S.max(-1, keepdims=True))
     A = E / E.sum(-1, keepdims=True) * P              # only kept entries are stored
     ref = np.einsum("bij,bjd->bid", A, V)
-    O, _ = oracle.attn_fwd(Q, K, V, P, flags=oracle.ATTN_PAPER_DENOM)
+    O, LSE = oracle.attn_fwd(Q, K, V, P, flags=oracle.ATTN_PAPER_DENOM)
     assert np.allclose(O, ref, rtol=1e-11, atol=1e-13)
+    # the row statistic of that variant: log of the literal Eq. 5 row sum (masked entries are exp(0))
+    assert np.allclose(LSE, np.log(np.exp(S).sum(-1)), rtol=1e-12, atol=0)
+    kept = P.sum(-1)                                   # and, term by term, Algorithm 6's sum
+    ref_sum = (np.exp(scale * np.einsum("bid,bjd->bij", Q, K)) * P).sum(-1) + (L - kept)[None, :]
+    assert np.allclose(np.exp(LSE), ref_sum, rtol=1e-12, atol=0)
+    # a row that keeps nothing still has the L masked entries in its denominator
+    P0 = P.copy()
+    P0[8:16, :] = 0
+    O0, LSE0 = oracle.attn_fwd(Q, K, V, P0, flags=oracle.ATTN_PAPER_DENOM)
+    assert np.all(O0[:, 8:16] == 0.0)
     # gradient of that variant against torch autograd of the same expression
     q, k, v = [torch.tensor(t, requires_grad=True) for t in (Q, K, V)]
     Pt = torch.tensor(P, dtype=torch.float64)

@@ -176,7 +176,8 @@ def test_fill_hand_traced_walkthroughs(case):
 
 def brute_force_fill(x: np.ndarray, t, force_diag=True) -> np.ndarray:
     """Reachability over the 'neighbours equal to their maximum' successor relation, written
-    independently of the recursion: breadth-first from every seed; reached cells above t are kept."""
+    independently of the oracle's walks: breadth-first over Python sets from every seed; reached
+    cells above t are kept."""
     nb = x.shape[0]
 
     def succ(r, c):
@@ -244,7 +245,7 @@ def test_fill_invariants():
     fl = oracle.fill(x, oracle.make_thresh_int(t))
     assert np.all(np.diag(fl) == 1)
     assert np.array_equal(fl - np.diag(np.diag(fl)), raw - np.diag(np.diag(raw)))
-    # constant map with t >= the constant marks nothing (tiny nb: the recursion is exponential)
+    # constant map with t >= the constant marks nothing
     const = np.full((5, 5), 4, dtype=np.int64)
     assert oracle.fill(const, oracle.make_thresh_int(4), force_diag=False).sum() == 0
     # ... and with t below the constant marks everything reachable: all but row 0 / col 0 seeds'
@@ -272,10 +273,50 @@ def test_fill_follows_a_dominant_column_and_a_dominant_diagonal():
     assert np.array_equal(fl, exp)
 
 
-def test_fill_budget_guard_reports_instead_of_hanging():
-    const = np.zeros((14, 14), dtype=np.int64)
-    with pytest.raises(RuntimeError):
-        oracle.fill(const, oracle.make_thresh_int(5), budget=100_000)
+def test_fill_on_large_plateaus_is_linear_work():
+    # all pooled values equal: every neighbour ties, a literal re-expansion of unmarked cells would
+    # be exponential; everything except (0, 0) is reachable
+    nb = 64
+    const = np.zeros((nb, nb), dtype=np.int64)
+    assert oracle.fill(const, oracle.make_thresh_int(5), force_diag=False).sum() == 0
+    full = oracle.fill(const, oracle.make_thresh_int(-1), force_diag=False)
+    assert full.sum() == nb * nb - 1 and full[0, 0] == 0
+
+
+def fill_by_predecessors(x: np.ndarray, t, force_diag=True) -> np.ndarray:
+    """The same set computed the other way round: moves only go down, right or down-right, so in
+    row-major order every predecessor of a cell is settled before the cell.  A cell is stepped onto
+    iff one of its three predecessors is a live cell (a seed of the first row / column, or itself
+    stepped onto), lies outside the last row and column, and sees the cell among the largest of
+    its own three neighbours."""
+    nb = x.shape[0]
+    live = np.zeros((nb, nb), dtype=bool)        # a walk stands on this cell at some point
+    stepped = np.zeros((nb, nb), dtype=bool)
+    live[0, :] = True
+    live[:, 0] = True
+    for r in range(nb):
+        for c in range(nb):
+            for pr, pc in ((r - 1, c), (r, c - 1), (r - 1, c - 1)):
+                if pr < 0 or pc < 0 or not live[pr, pc] or pr == nb - 1 or pc == nb - 1:
+                    continue
+                if x[r, c] == max(x[pr + 1, pc], x[pr, pc + 1], x[pr + 1, pc + 1]):
+                    stepped[r, c] = True
+            live[r, c] |= stepped[r, c]
+    fl = (stepped & (x > t)).astype(np.uint8)
+    if force_diag:
+        fl[np.arange(nb), np.arange(nb)] = 1
+    return fl
+
+
+@pytest.mark.parametrize("nb", [2, 3, 7, 16, 40])
+def test_fill_equals_predecessor_sweep_on_random_maps(nb):
+    rng = np.random.default_rng(100 + nb)
+    for trial in range(60):
+        hi = [2, 4, 50, 10**9][trial % 4]
+        x = rng.integers(0, hi, size=(nb, nb)).astype(np.int64)
+        t = int(rng.integers(-1, hi))
+        assert np.array_equal(oracle.fill(x, oracle.make_thresh_int(t)), fill_by_predecessors(x, t)), (x, t)
+        assert np.array_equal(brute_force_fill(x, t), fill_by_predecessors(x, t))
 
 
 def test_topk_variant_keeps_blocks_above_threshold_plus_diagonal():
