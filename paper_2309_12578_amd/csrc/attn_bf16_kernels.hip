@@ -312,8 +312,9 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
 
     float lsum = lacc[0];
-    if (paper_denom) {
-        // Algorithm 6: every masked entry of the row counts as a score of 0
+    if (paper_denom && n > 0) {
+        // Algorithm 6: every masked entry of the row counts as a score of 0 (a row that keeps nothing
+        // has no entry to normalise and stays at O = 0, LSE = -inf)
         const float masked = (float)(L - n * BS);
         const float mp = fmaxf(m, 0.f);
         const float a = exp2f(m - mp);

@@ -97,8 +97,9 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_kernel(
     }
 
     lsum = group_sum(lsum);
-    if (paper_denom) {
-        // Algorithm 6: every masked entry of the row counts as a score of 0
+    if (paper_denom && je > jb) {
+        // Algorithm 6: every masked entry of the row counts as a score of 0 (a row that keeps nothing
+        // has no entry to normalise and stays at O = 0, LSE = -inf)
         const float masked = (float)(L - (je - jb) * BS);
         const float mp = fmaxf(m, 0.f);
         const float a = exp2f(m - mp);

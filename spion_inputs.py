@@ -52,22 +52,45 @@ def _wl(name, cfg, layer, B, H, L, dtype, block, band, ns, sw, nob, filt, tm, tv
                     seed=1000 * cfg + layer)
 
 
-# Configurations 1-4 and the four layers of configuration 5.
+# Configurations 1-4 and the four layers of configuration 5.  The quantile of configurations 2-5
+# is chosen (scan over q in steps of 0.005 with the CPU oracle on the full head / batch mean) so
+# that the block density the flood fill ACHIEVES lands on the density the configuration names:
+# ~15 % / ~10 % / ~8 %, and 4 % to ~21 % over the layers of configuration 5.  The fill keeps only
+# cells a walk reaches, so the achieved density is below 1 - q, and it cannot exceed the share of
+# reachable cells whatever the threshold: 22.2 % on layer 3 of configuration 5, whose 25 % is
+# therefore out of reach (q = 0.25 gives 20.8 %).
 WORKLOADS: List[Workload] = [
     _wl("cfg1_tiny_f32_L256", 1, 0, 1, 1, 256, "f32", 16, 8, 3, 4, 0, 5, T_MEAN_KSTD, 1.0),
-    _wl("cfg2_bf16_L1024", 2, 0, 16, 4, 1024, "bf16", 32, 32, 8, 8, 0, 31, T_QUANTILE, 0.85),
-    _wl("cfg3_bf16_L2048", 3, 0, 8, 4, 2048, "bf16", 32, 48, 12, 8, 6, 31, T_QUANTILE, 0.90),
-    _wl("cfg4_bf16_L4096", 4, 0, 4, 4, 4096, "bf16", 64, 64, 16, 16, 0, 31, T_QUANTILE, 0.92),
-    _wl("cfg5_layer0", 5, 0, 4, 8, 4096, "bf16", 64, 32, 4, 16, 0, 31, T_QUANTILE, 0.96),
-    _wl("cfg5_layer1", 5, 1, 4, 8, 4096, "bf16", 64, 64, 10, 16, 0, 31, T_QUANTILE, 0.90),
-    _wl("cfg5_layer2", 5, 2, 4, 8, 4096, "bf16", 64, 128, 16, 16, 0, 31, T_QUANTILE, 0.83),
-    _wl("cfg5_layer3", 5, 3, 4, 8, 4096, "bf16", 64, 256, 24, 16, 0, 31, T_QUANTILE, 0.75),
+    _wl("cfg2_bf16_L1024", 2, 0, 16, 4, 1024, "bf16", 32, 32, 8, 8, 0, 31, T_QUANTILE, 0.77),
+    _wl("cfg3_bf16_L2048", 3, 0, 8, 4, 2048, "bf16", 32, 48, 12, 8, 6, 31, T_QUANTILE, 0.67),
+    _wl("cfg4_bf16_L4096", 4, 0, 4, 4, 4096, "bf16", 64, 64, 16, 16, 0, 31, T_QUANTILE, 0.88),
+    _wl("cfg5_layer0", 5, 0, 4, 8, 4096, "bf16", 64, 32, 4, 16, 0, 31, T_QUANTILE, 0.93),
+    _wl("cfg5_layer1", 5, 1, 4, 8, 4096, "bf16", 64, 64, 10, 16, 0, 31, T_QUANTILE, 0.71),
+    _wl("cfg5_layer2", 5, 2, 4, 8, 4096, "bf16", 64, 128, 16, 16, 0, 31, T_QUANTILE, 0.55),
+    _wl("cfg5_layer3", 5, 3, 4, 8, 4096, "bf16", 64, 256, 24, 16, 0, 31, T_QUANTILE, 0.25),
 ]
 
+# Kept blocks the CPU oracle finds on each workload (full head / batch mean); the CPU tests
+# recompute them, and the density targets above are asserted against these.
+EXPECTED_NNZB = {"cfg1_tiny_f32_L256": 19, "cfg2_bf16_L1024": 153, "cfg3_bf16_L2048": 411,
+                 "cfg4_bf16_L4096": 326, "cfg5_layer0": 156, "cfg5_layer1": 408, "cfg5_layer2": 655,
+                 "cfg5_layer3": 851}
+TARGET_DENSITY = {"cfg2_bf16_L1024": 0.15, "cfg3_bf16_L2048": 0.10, "cfg4_bf16_L4096": 0.08}
 
-def workload(name_or_cfg, layer: int = 0) -> Workload:
+# Second, named variant of configurations 2-5: q = 1 - target density, the setting earlier
+# measurements of this repository were taken with (sparser: 8.0 % / 4.1 % / 5.2 %, 2.1-10.4 %).
+Q_ONE_MINUS_TARGET = {"cfg2_bf16_L1024": 0.85, "cfg3_bf16_L2048": 0.90, "cfg4_bf16_L4096": 0.92,
+                      "cfg5_layer0": 0.96, "cfg5_layer1": 0.90, "cfg5_layer2": 0.83, "cfg5_layer3": 0.75}
+
+
+def workload(name_or_cfg, layer: int = 0, variant: str = "density") -> Workload:
+    """variant "density": quantile tuned to the named density; "one_minus_target": q = 1 - target."""
     for w in WORKLOADS:
         if w.name == name_or_cfg or (w.cfg == name_or_cfg and w.layer == layer):
+            if variant == "one_minus_target" and w.name in Q_ONE_MINUS_TARGET:
+                return dataclasses.replace(w, thresh_value=Q_ONE_MINUS_TARGET[w.name])
+            if variant not in ("density", "one_minus_target"):
+                raise KeyError(variant)
             return w
     raise KeyError(name_or_cfg)
 

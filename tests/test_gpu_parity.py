@@ -4,6 +4,8 @@ Bars: pattern outputs (pool_sum, fl_out, BSR, BSC, nnzb) bit-exact; attention ou
 gradients within 1e-5 (fp32) / 2e-2 (bf16), both as relative Frobenius error and as
 max|x - ref| / max|ref|, against the fp64 oracle fed the same (already rounded) input values.
 """
+import functools
+
 import numpy as np
 import pytest
 import torch
@@ -40,6 +42,15 @@ def _rel_errors(x, ref):
     return fro, mx
 
 
+@functools.lru_cache(maxsize=2)
+def _workload_inputs(name):
+    """Q, K, V, dO and the score map averaged over ALL (batch, head) slices: the very map, and so
+    the very index, that the benchmark times."""
+    w = si.workload(name)
+    Q, K, V, dO = si.make_qkv_do(w)
+    return Q, K, V, dO, si.make_score_map(w, Q, K)
+
+
 def _check_pattern(sp, A, block, filt, mode, value, flags=0, variant="CF"):
     ref = oracle.generate_pattern(A, block, filt, mode, value, variant=variant)
     pat = sp.generate_pattern(_dev(A), block, filt, mode, value, flags=flags)
@@ -62,13 +73,15 @@ def _check_pattern(sp, A, block, filt, mode, value, flags=0, variant="CF"):
 @pytest.mark.parametrize("name", [w.name for w in si.WORKLOADS])
 def test_pattern_bit_exact_on_workloads(sp, name):
     w = si.workload(name)
-    bh = min(w.B * w.H, 8)          # the averaged map of 8 heads has the same structure; keeps CPU time low
-    Q, K, _, _ = si.make_qkv_do(w, bh_limit=bh)
-    A = si.make_score_map(w, Q, K)
+    A = _workload_inputs(name)[4]
     pat, ref = _check_pattern(sp, A, w.block, w.filt, w.thresh_mode, w.thresh_value)
     dens = ref["nnzb"] / float(w.nb * w.nb)
     print(f"{name}: nnzb={ref['nnzb']} density={dens:.4f}")
-    assert 0.0 < dens < 0.6
+    assert ref["nnzb"] == si.EXPECTED_NNZB[name]
+    # the sparser variant (q = 1 - target density) of the same map
+    w1 = si.workload(name, variant="one_minus_target")
+    if w1.thresh_value != w.thresh_value:
+        _check_pattern(sp, A, w.block, w.filt, w1.thresh_mode, w1.thresh_value)
 
 
 @pytest.mark.parametrize("L,block,filt", [(64, 16, 1), (128, 16, 5), (256, 32, 31), (256, 64, 31),
@@ -405,15 +418,32 @@ def test_attention_tall_columns_are_split_into_chunks(sp, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_attention_paper_denominator_and_explicit_scale(sp, dtype):
-    block, nb, BH, d = 16, 6, 2, 64
+@pytest.mark.parametrize("block", [16, 32, 64])
+def test_attention_paper_denominator_and_explicit_scale(sp, dtype, block):
+    """Algorithm 6's denominator (every masked entry of a row counted as a score of 0) and an explicit
+    scale, on every kernel family: block 32 / 64 in bf16 take the tuned kernels, the rest the generic
+    ones.  The mask has a row without its diagonal block, a row that keeps a single off-diagonal
+    block, a full row and a row that keeps nothing."""
+    nb, BH, d = 6, 2, 64
     L = nb * block
-    rng = np.random.default_rng(4)
+    rng = np.random.default_rng(4 + block)
     Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), dtype)
                    for _ in range(4)]
     fl = si.random_block_mask(nb, 0.4, seed=9)
+    fl[1, 1] = 0
+    fl[1, 4] = 1                                             # row 1: no diagonal block
+    fl[2, :] = 0
+    fl[2, 5] = 1                                             # row 2: one off-diagonal block
+    fl[3, :] = 1                                             # row 3: nothing masked (both sums agree)
+    fl[4, :] = 0                                             # row 4: nothing kept
     _run_attention_case(sp, Q, K, V, dO, fl, block, dtype, flags=sp.SPION_ATTN_PAPER_DENOM)
     _run_attention_case(sp, Q, K, V, dO, fl, block, dtype, scale=0.2)
+    _run_attention_case(sp, Q, K, V, dO, fl, block, dtype, flags=sp.SPION_ATTN_PAPER_DENOM, scale=0.07)
+    # scores of a few hundred: the kept maximum is far above the masked entries' 0
+    big = [si.round_to_dtype(t * s_, dtype) for t, s_ in zip((Q, K, V, dO), (6.0, 6.0, 1.0, 1.0))]
+    _run_attention_case(sp, *big, fl, block, dtype, flags=sp.SPION_ATTN_PAPER_DENOM)
+    # every kept score negative (around -5): the row maximum lies below the masked entries' 0
+    _run_attention_case(sp, np.abs(Q), -np.abs(K), V, dO, fl, block, dtype, flags=sp.SPION_ATTN_PAPER_DENOM)
 
 
 def test_attention_large_scores_stay_finite(sp):
@@ -428,16 +458,18 @@ def test_attention_large_scores_stay_finite(sp):
 
 @pytest.mark.parametrize("name,heads", [("cfg1_tiny_f32_L256", None), ("cfg2_bf16_L1024", 16),
                                         ("cfg3_bf16_L2048", 8), ("cfg4_bf16_L4096", 4),
-                                        ("cfg5_layer0", 2), ("cfg5_layer3", 2)])
+                                        ("cfg5_layer0", 2), ("cfg5_layer1", 2), ("cfg5_layer2", 2),
+                                        ("cfg5_layer3", 2)])
 def test_attention_workloads_full_size(sp, name, heads):
     """Full-size launch (all batch items and heads, the configuration the benchmark times) with the
-    pattern produced by spion_pattern; the oracle checks a spread of (batch, head) slices."""
+    pattern spion_pattern produces from the mean over all (batch, head) slices, i.e. the benchmark's
+    own index; the oracle checks a spread of (batch, head) slices."""
     w = si.workload(name)
-    Q, K, V, dO = si.make_qkv_do(w)
-    A = si.make_score_map(w, Q[:8], K[:8])
+    Q, K, V, dO, A = _workload_inputs(name)
     pat = sp.generate_pattern(_dev(A), w.block, w.filt, w.thresh_mode, w.thresh_value)
     fl = pat.fl_out.cpu().numpy()
     assert np.array_equal(fl, oracle.generate_pattern(A, w.block, w.filt, w.thresh_mode, w.thresh_value)["fl_out"])
+    assert pat.nnzb == si.EXPECTED_NNZB[name]
     BH = w.B * w.H
     sel = None if heads is None else sorted(set(np.linspace(0, BH - 1, heads).astype(int).tolist()))
     errs = _run_attention_case(sp, Q, K, V, dO, fl, w.block, w.dtype, heads=sel)
