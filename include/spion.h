@@ -15,7 +15,8 @@
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its comment says HOST.  The caller owns all buffers;
- *     the library never allocates or frees device memory and keeps no state between calls.
+ *     the library never allocates or frees device memory and keeps no state between calls (the one
+ *     exception, the built-in scratch array of spion_pattern_static, is described there).
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the null stream) and
  *     the call returns without synchronising.  Outputs are valid once the stream reaches that point.
  *   - Return value: SPION_OK (0) or a negative spion_status.  Argument errors are detected on the
@@ -38,6 +39,7 @@ extern "C" {
 #endif
 
 #define SPION_MAX_NB 1024 /* largest supported number of block rows L / block */
+#define SPION_STATIC_MAX_NB 256 /* largest L / block spion_pattern_static accepts */
 
 typedef enum {
     SPION_OK = 0,
@@ -47,7 +49,8 @@ typedef enum {
     SPION_ERR_WORKSPACE = -4, /* workspace missing, misaligned (256 B) or too small */
     SPION_ERR_PARAM = -5,     /* even filter, filter too large, quantile outside [0,1], bad flags */
     SPION_ERR_INDEX = -6,     /* malformed block-sparse index (written by spion_index_check only) */
-    SPION_ERR_HIP = -7        /* a HIP runtime call failed (launch error) */
+    SPION_ERR_HIP = -7,       /* a HIP runtime call failed (launch error) */
+    SPION_ERR_TOO_LARGE = -8  /* spion_pattern_static only: L / block > SPION_STATIC_MAX_NB */
 } spion_status;
 
 typedef enum { SPION_F32 = 0, SPION_BF16 = 1 } spion_dtype;
@@ -96,6 +99,23 @@ int spion_pattern(const float *A_s, const spion_pattern_params *p, uint8_t *fl_o
                   int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx, int32_t *bsr_pos,
                   int32_t *nnzb, int64_t *pool_sum, void *workspace, size_t workspace_bytes,
                   void *hip_stream);
+
+/*
+ * spion_pattern for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and
+ * results as spion_pattern without `workspace` / `workspace_bytes`: the scratch (pooled sums, cell
+ * bits, transposed mask, positions) lives in a 1 MiB array that is part of the library's device
+ * image, one copy per GPU, held until the process ends.  The call allocates and frees nothing.
+ *   - L / block must not exceed SPION_STATIC_MAX_NB (256; e.g. L = 16384 at block 64), else
+ *     SPION_ERR_TOO_LARGE is returned and nothing is enqueued.
+ *   - The array's address is looked up on the first call on each device (the device current at the
+ *     call, which must be the stream's device); make that first call outside a graph capture.
+ *   - All calls on one GPU share the array: the kernels clear what they need at zero themselves, but
+ *     two calls that overlap on the same GPU (different streams, or graphs replayed concurrently) race.
+ */
+int spion_pattern_static(const float *A_s, const spion_pattern_params *p, uint8_t *fl_out,
+                         int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx,
+                         int32_t *bsr_pos, int32_t *nnzb, int64_t *pool_sum, void *hip_stream);
 
 /*
  * Checks a block-sparse index (the compressed form of the pattern, Section 4.3) before it is handed

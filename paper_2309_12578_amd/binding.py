@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.spion_pattern_workspace_bytes.argtypes = [i32, i32]
     lib.spion_pattern.restype = ctypes.c_int
     lib.spion_pattern.argtypes = [vp, ctypes.POINTER(_PatternParams)] + [vp] * 8 + [vp, sz, vp]
+    lib.spion_pattern_static.restype = ctypes.c_int
+    lib.spion_pattern_static.argtypes = [vp, ctypes.POINTER(_PatternParams)] + [vp] * 8 + [vp]
     lib.spion_index_check.restype = ctypes.c_int
     lib.spion_index_check.argtypes = [vp] * 5 + [i32, i32, vp, vp]
     lib.spion_score_mean.restype = ctypes.c_int
@@ -130,6 +132,16 @@ def spion_pattern(A_s, L, block, filt, thresh_mode, thresh_value, fl_out, row_pt
                               _ptr(workspace), ws_bytes, _stream(stream))
     if rc != 0:
         raise SpionError(rc, "spion_pattern")
+
+
+def spion_pattern_static(A_s, L, block, filt, thresh_mode, thresh_value, fl_out, row_ptr, col_idx, col_ptr,
+                         row_idx, bsr_pos, nnzb, pool_sum, stream=None, flags: int = 0) -> None:
+    p = _PatternParams(L, block, filt, thresh_mode, float(thresh_value), flags, 0)
+    rc = load().spion_pattern_static(_ptr(A_s), ctypes.byref(p), _ptr(fl_out), _ptr(row_ptr), _ptr(col_idx),
+                                     _ptr(col_ptr), _ptr(row_idx), _ptr(bsr_pos), _ptr(nnzb), _ptr(pool_sum),
+                                     _stream(stream))
+    if rc != 0:
+        raise SpionError(rc, "spion_pattern_static")
 
 
 def spion_index_check(row_ptr, col_idx, col_ptr, row_idx, bsr_pos, nb: int, nnzb: int, status,

@@ -4,12 +4,39 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/spion.h"
 #include "spion_internal.h"
+
+// Built-in scratch of spion_pattern_static: the pattern workspace (pooled sums, cell bits, the
+// transposed mask, positions) for up to SPION_STATIC_MAX_NB^2 blocks.  Every GPU the library runs
+// on holds its own copy of this array at its own address until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress: kernels and copies are given the resolved address.
+constexpr size_t kStaticScratchBytes = 1u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // per device: address of `scratch` on that device
+
+// Address of `scratch` on the current device, resolved once per device (first call on it) with that
+// device current.
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPION_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SPION_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SPION_OK;
+}
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -76,6 +103,7 @@ const char* spion_strerror(int status) {
         case SPION_ERR_PARAM: return "invalid parameter value";
         case SPION_ERR_INDEX: return "malformed block-sparse index";
         case SPION_ERR_HIP: return "HIP runtime error";
+        case SPION_ERR_TOO_LARGE: return "problem exceeds the built-in scratch buffer (L / block > SPION_STATIC_MAX_NB)";
         default: return "unknown status";
     }
 }
@@ -86,14 +114,16 @@ size_t spion_pattern_workspace_bytes(int32_t L, int32_t block) {
     return PatternWs(nb * nb).total;
 }
 
-int spion_pattern(const float* A_s, const spion_pattern_params* p, uint8_t* fl_out, int32_t* row_ptr,
-                  int32_t* col_idx, int32_t* col_ptr, int32_t* row_idx, int32_t* bsr_pos, int32_t* nnzb,
-                  int64_t* pool_sum, void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int pattern_impl(const float* A_s, const spion_pattern_params* p, uint8_t* fl_out, int32_t* row_ptr,
+                        int32_t* col_idx, int32_t* col_ptr, int32_t* row_idx, int32_t* bsr_pos, int32_t* nnzb,
+                        int64_t* pool_sum, void* workspace, size_t workspace_bytes, void* hip_stream,
+                        bool use_static_scratch) {
     if (!A_s || !p || !fl_out || !row_ptr || !col_idx || !nnzb) return SPION_ERR_NULL;
     const bool any_bsc = col_ptr || row_idx || bsr_pos;
     if (any_bsc && !(col_ptr && row_idx && bsr_pos)) return SPION_ERR_NULL;
     if (!shape_ok(p->L, p->block)) return SPION_ERR_SHAPE;
     const int32_t bs = p->block, nb = p->L / bs;
+    if (use_static_scratch && nb > SPION_STATIC_MAX_NB) return SPION_ERR_TOO_LARGE;
     if (p->filter < 1 || (p->filter % 2) == 0 || (p->filter - 1) / 2 >= bs) return SPION_ERR_PARAM;
     if (p->reserved != 0 || (p->flags & ~SPION_PATTERN_NO_FILL)) return SPION_ERR_PARAM;
     const int64_t n = (int64_t)nb * nb;
@@ -125,6 +155,12 @@ int spion_pattern(const float* A_s, const spion_pattern_params* p, uint8_t* fl_o
         default: return SPION_ERR_PARAM;
     }
     const PatternWs ws((size_t)n);
+    if (use_static_scratch) {
+        // every argument has passed validation; only now is the device touched
+        const int rc = static_scratch(&workspace);
+        if (rc != SPION_OK) return rc;
+        workspace_bytes = kStaticScratchBytes;
+    }
     if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < ws.total)
         return SPION_ERR_WORKSPACE;
     char* w = static_cast<char*>(workspace);
@@ -141,6 +177,20 @@ int spion_pattern(const float* A_s, const spion_pattern_params* p, uint8_t* fl_o
                                      col_ptr, row_idx, bsr_pos, nnzb, st) != hipSuccess)
         return SPION_ERR_HIP;
     return SPION_OK;
+}
+
+int spion_pattern(const float* A_s, const spion_pattern_params* p, uint8_t* fl_out, int32_t* row_ptr,
+                  int32_t* col_idx, int32_t* col_ptr, int32_t* row_idx, int32_t* bsr_pos, int32_t* nnzb,
+                  int64_t* pool_sum, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return pattern_impl(A_s, p, fl_out, row_ptr, col_idx, col_ptr, row_idx, bsr_pos, nnzb, pool_sum, workspace,
+                        workspace_bytes, hip_stream, false);
+}
+
+int spion_pattern_static(const float* A_s, const spion_pattern_params* p, uint8_t* fl_out, int32_t* row_ptr,
+                         int32_t* col_idx, int32_t* col_ptr, int32_t* row_idx, int32_t* bsr_pos,
+                         int32_t* nnzb, int64_t* pool_sum, void* hip_stream) {
+    return pattern_impl(A_s, p, fl_out, row_ptr, col_idx, col_ptr, row_idx, bsr_pos, nnzb, pool_sum, nullptr, 0,
+                        hip_stream, true);
 }
 
 int spion_score_mean(const void* A_maps, int32_t n_maps, int32_t L, int32_t dtype, float* A_s,

@@ -68,6 +68,18 @@ def test_argument_errors_are_reported_before_any_launch():
     partial_bsc[6] = none                                                   # row_idx missing, others given
     assert lib.spion_pattern(*partial_bsc) == -1
 
+    # the variant with the built-in scratch validates the same way and refuses what does not fit
+    sargs = [fake, ctypes.byref(p)] + [fake] * 8 + [none]
+    nul = list(sargs)
+    nul[2] = none
+    assert lib.spion_pattern_static(*nul) == -1
+    big = _PatternParams(8192, 16, 5, sp.SPION_T_QUANTILE, 0.5, 0, 0)            # nb = 512 > 256
+    sargs[1] = ctypes.byref(big)
+    assert lib.spion_pattern_static(*sargs) == -8
+    even = _PatternParams(256, 16, 4, sp.SPION_T_QUANTILE, 0.5, 0, 0)
+    sargs[1] = ctypes.byref(even)
+    assert lib.spion_pattern_static(*sargs) == -5
+
     ap = _AttnParams(1, 1, 256, 64, 16, sp.SPION_F32, 0.0, 0)
     fargs = [fake] * 7 + [19, ctypes.byref(ap), none, 0, none]
     nul = list(fargs)
