@@ -24,7 +24,7 @@
  *   - Tensors Q, K, V, O, dO, dQ, dK, dV are [B, H, L, d] contiguous (d fastest) in the element type
  *     named by `dtype`; LSE is fp32 [B, H, L].  Supported: d == 64, block in {16, 32, 64},
  *     L % block == 0, L / block <= SPION_MAX_NB, and B * H * (L / block) < 2^31 (one workgroup per
- *     block row and head; the backward also needs B * H * (nnzb / 10 + L / block) < 2^31).  A shape
+ *     block row and head; the backward also needs B * H * (nnzb / 16 + 2 L / block) < 2^31).  A shape
  *     outside these limits is SPION_ERR_SHAPE.
  *   - One pattern (one BSR/BSC index) is shared by all batch items and heads of a layer.
  */
@@ -64,6 +64,12 @@ typedef enum {
 
 /* spion_pattern_params.flags */
 #define SPION_PATTERN_NO_FILL 1u /* SPION-C variant (Section 5): keep every block above t, no flood fill */
+/* The two halves of Algorithm 3 on their own.  Eq. 3 and Eq. 4 are linear in A_s and the pooled sums
+ * are exact integers, so the pool_sum maps of partial score maps (one per GPU of a sharded batch,
+ * say) can be added element by element by the caller and handed to the second half. */
+#define SPION_PATTERN_POOL_ONLY 2u /* Eq. 3 + Eq. 4 only: writes pool_sum (required) and nothing else */
+#define SPION_PATTERN_FROM_POOL 4u /* threshold, flood fill, compaction from a given pool_sum (required,
+                                      read only); A_s is not read and may be NULL */
 
 typedef struct {
     int32_t L;            /* sequence length */
@@ -92,7 +98,8 @@ size_t spion_pattern_workspace_bytes(int32_t L, int32_t block);
  *             The three may all be NULL if the caller needs no backward pass.
  *   nnzb      device int32 scalar, number of kept blocks (== row_ptr[nb]).
  *   pool_sum  optional [nb, nb] int64 output: block sums of the convolution output in fixed point,
- *             pool_out = pool_sum / (block^2 * 2^40).  May be NULL.
+ *             pool_out = pool_sum / (block^2 * 2^40).  May be NULL unless a SPION_PATTERN_*_POOL flag
+ *             is set.  With SPION_PATTERN_POOL_ONLY every other output pointer may be NULL.
  *   workspace at least spion_pattern_workspace_bytes(L, block) bytes, 256-byte aligned.
  */
 int spion_pattern(const float *A_s, const spion_pattern_params *p, uint8_t *fl_out, int32_t *row_ptr,
@@ -133,9 +140,10 @@ int spion_index_check(const int32_t *row_ptr, const int32_t *col_idx, const int3
 
 /* spion_attn_params.flags */
 #define SPION_ATTN_PAPER_DENOM 1u /* add Algorithm 6's exp(-max) * (L - kept) term to the row sum */
-/* spion_attn_bwd only: run one of its two phases (for per-phase timing).  The key-side phase reads
- * what the query-side phase of an earlier call with the same arguments and workspace left there
- * (delta, the row statistics in log2 units, the key-side work list). */
+/* spion_attn_bwd only: run one of its two sides on its own (for per-side timing).  The bf16 kernels
+ * for block 32 / 64 compute both sides in one launch and either side alone is self-contained; in the
+ * other kernels the key side reads what the query side of an earlier call with the same arguments
+ * and workspace left there (delta, the key-side work list). */
 #define SPION_ATTN_BWD_QUERY_SIDE_ONLY 2u /* delta and dQ only */
 #define SPION_ATTN_BWD_KEY_SIDE_ONLY 4u   /* dK and dV only */
 
@@ -199,6 +207,16 @@ int spion_score_mean(const void *A_maps, int32_t n_maps, int32_t L, int32_t dtyp
 size_t spion_frobenius_workspace_bytes(void);
 int spion_frobenius_distance(const float *A_prev, const float *A_cur, int64_t n, double *out,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Measurement aid (Section 5 reports time and memory; this library reports them against the HBM
+ * roofline): copies n_bytes (a positive multiple of 16384; src, dst 16-byte aligned, not overlapping)
+ * with the access shapes of the attention kernels - 16 bytes per lane from memory straight into LDS,
+ * 16 bytes per lane row stores out - reading and writing every byte exactly once.  A launch of known
+ * traffic: what a profiler's memory counters report for it is the scale for their readings of the
+ * other kernels in the same run.
+ */
+int spion_copy_yardstick(const void *src, void *dst, size_t n_bytes, void *hip_stream);
 
 /* Static, NUL-terminated description of a spion_status value. */
 const char *spion_strerror(int status);

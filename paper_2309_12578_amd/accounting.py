@@ -40,8 +40,9 @@ def algorithmic_bytes(kernel: str, bh: int, L: int, d: int, elem_bytes: int) -> 
     """Compulsory HBM traffic of one launch: every tensor the step needs, moved exactly once.
 
     fwd        reads Q, K, V; writes O and LSE
-    bwd_query  reads Q, K, V, O, dO, LSE; writes dQ and delta
-    bwd_key    reads Q, K, V, dO, LSE, delta; writes dK, dV
+    bwd        reads Q, K, V, O, dO, LSE; writes dQ, dK, dV (the whole backward call)
+    bwd_query  the query side of the backward run alone: reads Q, K, V, O, dO, LSE; writes dQ
+    bwd_key    the key side run alone: reads Q, K, V, O, dO, LSE; writes dK, dV
     path       forward + backward of an ideal fused implementation: reads Q, K, V (fwd), writes O;
                reads Q, K, V, O, dO, writes dQ, dK, dV (12 tensor passes) plus LSE / delta vectors
     """
@@ -49,10 +50,12 @@ def algorithmic_bytes(kernel: str, bh: int, L: int, d: int, elem_bytes: int) -> 
     vec = bh * L * 4
     if kernel == "fwd":
         return 4 * t + vec
+    if kernel == "bwd":
+        return 8 * t + vec
     if kernel == "bwd_query":
-        return 6 * t + 2 * vec
+        return 6 * t + vec
     if kernel == "bwd_key":
-        return 6 * t + 2 * vec
+        return 7 * t + vec
     if kernel == "path":
         return 12 * t + 2 * vec
     raise ValueError(kernel)

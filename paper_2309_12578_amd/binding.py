@@ -18,6 +18,8 @@ _LIB_PATH = os.path.join(_HERE, "libspion.so")
 SPION_F32, SPION_BF16 = 0, 1
 SPION_T_ABS, SPION_T_QUANTILE, SPION_T_MEAN_KSTD = 0, 1, 2
 SPION_PATTERN_NO_FILL = 1
+SPION_PATTERN_POOL_ONLY = 2
+SPION_PATTERN_FROM_POOL = 4
 SPION_ATTN_PAPER_DENOM = 1
 SPION_ATTN_BWD_QUERY_SIDE_ONLY = 2
 SPION_ATTN_BWD_KEY_SIDE_ONLY = 4
@@ -76,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.spion_frobenius_workspace_bytes.argtypes = []
     lib.spion_frobenius_distance.restype = ctypes.c_int
     lib.spion_frobenius_distance.argtypes = [vp, vp, ctypes.c_int64, vp, vp, sz, vp]
+    lib.spion_copy_yardstick.restype = ctypes.c_int
+    lib.spion_copy_yardstick.argtypes = [vp, vp, sz, vp]
     lib.spion_attn_workspace_bytes.restype = sz
     lib.spion_attn_workspace_bytes.argtypes = [ctypes.POINTER(_AttnParams), i32, i32]
     lib.spion_attn_fwd.restype = ctypes.c_int
@@ -168,6 +172,12 @@ def spion_frobenius_distance(A_prev, A_cur, n: int, out, workspace, stream=None)
                                          ws_bytes, _stream(stream))
     if rc != 0:
         raise SpionError(rc, "spion_frobenius_distance")
+
+
+def spion_copy_yardstick(src, dst, n_bytes: int, stream=None) -> None:
+    rc = load().spion_copy_yardstick(_ptr(src), _ptr(dst), int(n_bytes), _stream(stream))
+    if rc != 0:
+        raise SpionError(rc, "spion_copy_yardstick")
 
 
 def _attn_params(B, H, L, d, block, dtype, scale, flags) -> _AttnParams:

@@ -28,6 +28,7 @@ SOURCES = [
     # instructions, and the AGPR form costs a register copy per value per step
     ("attn_kernels.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
     ("attn_bf16_kernels.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
+    ("attn_bwd_bf16_kernels.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form"]),
 ]
 
 

@@ -160,20 +160,22 @@ __device__ __forceinline__ void store_quad(T* dst, f32x4 v) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Key-side work list.  Vertical stripes give block columns with up to nb kept rows next to columns
-// with one or two, so the key-side kernel does not take one column per workgroup: a column with cnt
-// kept rows is cut into nch = ceil(cnt / kChunk) near-equal chunks, each a work item.  A column with
-// one chunk writes dK / dV directly; the chunks of a longer column write fp32 partial tiles into
-// numbered slots that a second kernel adds up in chunk order (deterministic).  The list is the same
-// for every head; one wave of the query-side kernel (which always runs first) builds it.
+// Key-side work items.  Vertical stripes give block columns with up to nb kept rows next to columns
+// with one or two, so the key side does not take one column per workgroup: a column with cnt kept
+// rows is cut into nch = ceil(cnt / kChunk) near-equal chunks, each a work item.  A column with one
+// chunk writes dK / dV directly; the chunks of a longer column write fp32 partial tiles into numbered
+// slots that a second kernel adds up in chunk order (deterministic).  The list is the same for every
+// head.  The generic kernels read it from the workspace, where one wave of their query-side kernel
+// (which runs first) builds it:
 //   sched[w]   = {J, kb, ke, slot}: BSC entries [kb, ke) of column J; slot < 0: write final output;
 //                J < 0: unused work item
-//   sched[w_max + w] = the first four block rows of the item, row_idx[kb .. kb + 3] clamped to the
-//                item: a workgroup gets them with the item in one round trip instead of two
+//   sched[w_max + w] = the first four block rows of the item (unused by the generic kernels)
 //   split[m]   = {J, first slot, nch, 0} for the m-th split column; J < 0: unused entry
+// The tuned bf16 backward derives the same items in every workgroup from col_ptr instead.
 // ------------------------------------------------------------------------------------------------
 #ifndef SPION_KEY_CHUNK
-#define SPION_KEY_CHUNK 10   // kept rows per key-side work item (build-time tunable; 8-12 measure alike)
+#define SPION_KEY_CHUNK 16   // kept rows per key-side work item (build-time tunable; 10-16 measure alike,
+                             // shorter chunks cost partial-tile traffic, longer ones the longest chain)
 #endif
 constexpr int kChunk = SPION_KEY_CHUNK;
 

@@ -325,7 +325,7 @@ size_t attn_bwd_workspace_bytes(int BH, int L, int bs, int nb, int nnzb) {
 bool attn_bwd_grids_fit(int BH, int L, int bs, int nb, int nnzb) {
     const BwdWorkspace ws(BH, L, bs, nb, nnzb);
     const int64_t limit = 0x7fffffffll;
-    return (int64_t)ws.w_max * BH <= limit && (int64_t)ws.split_max * BH * (bs / 16) <= limit;
+    return (int64_t)(ws.w_max + nb) * BH <= limit && (int64_t)ws.split_max * BH * (bs / 16) <= limit;
 }
 
 BwdWorkspace::BwdWorkspace(int BH, int L, int bs, int nb, int nnzb) {
@@ -358,44 +358,37 @@ static hipError_t bwd_t(const AttnShape& s, const void* Q, const void* K, const 
     const BwdWorkspace ws(s.BH, s.L, s.bs, s.nb, nnzb);
     char* base = static_cast<char*>(workspace);
     float* delta = reinterpret_cast<float*>(base + ws.delta_off);
-    float* lse2 = delta + (size_t)s.BH * s.L;   // written by the tuned query-side kernel for the key side
     int4* sched = reinterpret_cast<int4*>(base + ws.sched_off);
     int4* split = reinterpret_cast<int4*>(base + ws.split_off);
     float* partial = reinterpret_cast<float*>(base + ws.partial_off);
     const dim3 block(BS * 4);
-    constexpr bool kTuned = sizeof(T) == 2 && BS >= 32;
-    if constexpr (kTuned) {
+    if constexpr (sizeof(T) == 2 && BS >= 32) {
+        // tuned bf16 path: one launch for both sides (it needs no delta, work list or split list in the
+        // workspace), plus the small reduction of the partial tiles
+        return bwd_bf16<BS>(s, Q, K, V, O, dO, LSE, dQ, dK, dV, row_ptr, col_idx, col_ptr, row_idx, nnzb, ws.w_max,
+                            ws.split_max, ws.n_slots, partial, st);
+    } else {
         if (s.bwd_phases & 1) {
-            const hipError_t e = bwd_dq_bf16<BS>(s, Q, K, V, O, dO, LSE, dQ, delta, lse2, row_ptr, col_idx,
-                                                 col_ptr, row_idx, ws.w_max, ws.split_max, sched, split, st);
+            attn_bwd_dq_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
+                static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                static_cast<const T*>(O), static_cast<const T*>(dO), LSE, static_cast<T*>(dQ), delta,
+                row_ptr, col_idx, col_ptr, row_idx, ws.w_max, ws.split_max, sched, split, s.L, s.nb, s.scale,
+                s.scale * kLog2e);
+            const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
-    } else if (s.bwd_phases & 1) {
-        attn_bwd_dq_kernel<T, BS><<<dim3((unsigned)(s.nb * s.BH)), block, 0, st>>>(
-            static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-            static_cast<const T*>(O), static_cast<const T*>(dO), LSE, static_cast<T*>(dQ), delta,
-            row_ptr, col_idx, col_ptr, row_idx, ws.w_max, ws.split_max, sched, split, s.L, s.nb, s.scale,
-            s.scale * kLog2e);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    if (s.bwd_phases & 2) {
-        if constexpr (kTuned) {
-            const hipError_t e = bwd_dkv_bf16<BS>(s, Q, K, V, dO, lse2, delta, dK, dV, row_idx, sched, ws.w_max,
-                                                  ws.n_slots, partial, st);
+        if (s.bwd_phases & 2) {
+            attn_bwd_dkv_kernel<T, BS><<<dim3((unsigned)(ws.w_max * s.BH)), block, 0, st>>>(
+                static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                static_cast<const T*>(dO), LSE, delta, static_cast<T*>(dK), static_cast<T*>(dV), row_idx,
+                sched, ws.w_max, ws.n_slots, partial, s.L, s.scale, s.scale * kLog2e);
+            const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
-        } else {
-        attn_bwd_dkv_kernel<T, BS><<<dim3((unsigned)(ws.w_max * s.BH)), block, 0, st>>>(
-            static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-            static_cast<const T*>(dO), LSE, delta, static_cast<T*>(dK), static_cast<T*>(dV), row_idx,
-            sched, ws.w_max, ws.n_slots, partial, s.L, s.scale, s.scale * kLog2e);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+            attn_bwd_dkv_reduce_kernel<T, BS><<<dim3((unsigned)(ws.split_max * s.BH * (BS / 16))), dim3(256), 0, st>>>(
+                partial, split, ws.split_max, ws.n_slots, static_cast<T*>(dK), static_cast<T*>(dV), s.L, s.scale);
         }
-        attn_bwd_dkv_reduce_kernel<T, BS><<<dim3((unsigned)(ws.split_max * s.BH * (BS / 16))), dim3(256), 0, st>>>(
-            partial, split, ws.split_max, ws.n_slots, static_cast<T*>(dK), static_cast<T*>(dV), s.L, s.scale);
+        return hipGetLastError();
     }
-    return hipGetLastError();
 }
 
 #define SPION_DISPATCH(FN, ...)                                                   \

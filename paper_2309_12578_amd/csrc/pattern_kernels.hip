@@ -17,20 +17,6 @@
 
 namespace spion {
 
-// Developer build only (-DSPION_KERNEL_TRACE): timestamps of the stages of pattern_finish_kernel.
-#ifdef SPION_KERNEL_TRACE
-__device__ long long* spion_pattern_trace_buf = nullptr;
-void set_pattern_trace_buf(long long* p) {
-    (void)hipMemcpyToSymbol(HIP_SYMBOL(spion_pattern_trace_buf), &p, sizeof(p));
-}
-#define SPION_PTP(slot)                                                                        \
-    do {                                                                                       \
-        if (threadIdx.x == 0 && spion_pattern_trace_buf) spion_pattern_trace_buf[slot] = wall_clock64(); \
-    } while (0)
-#else
-#define SPION_PTP(slot) do { } while (0)
-#endif
-
 // ------------------------------------------------------------------------------------------------
 // conv + pool
 // ------------------------------------------------------------------------------------------------
@@ -50,6 +36,17 @@ void set_pattern_trace_buf(long long* p) {
 // Fixed point without 64-bit arithmetic in the inner loop: for |a| <= 1, x = a * 2^20 is exact in
 // fp32, hi = floor(x), lo = rint((x - hi) * 2^20) are exact integers of at most 21 bits and
 // a_q = hi * 2^20 + lo == rint(a * 2^40) with ties to even.
+// Build-time tunables of conv_pool_kernel.  Measured at L = 4096, block 64 (cold map): 2 workgroups of
+// 256 threads per compute unit, each walking 8 input blocks, beat both 1 and 3-16 per compute unit
+// (one workgroup per block, the shape without the loop, is 25 % slower); the sub-tile shape (16 x 16,
+// 8 x 32 or 4 x 64 scores per wave instruction) makes no difference.
+#ifndef SPION_CONV_WGS_PER_CU
+#define SPION_CONV_WGS_PER_CU 2
+#endif
+#ifndef SPION_CONV_SW
+#define SPION_CONV_SW 16
+#endif
+
 __device__ __forceinline__ int isect(int lo_a, int hi_a, int lo_b, int hi_b) {
     const int lo = lo_a > lo_b ? lo_a : lo_b;
     const int hi = hi_a < hi_b ? hi_a : hi_b;
@@ -60,37 +57,51 @@ __device__ __forceinline__ int isect(int lo_a, int hi_a, int lo_b, int hi_b) {
 __device__ __forceinline__ long long shfl_xor_i64(long long v, int mask) { return __shfl_xor(v, mask); }
 
 // slots: 0 (0,0)  1 (-1,0)  2 (+1,0)  3 (0,-1)  4 (0,+1)  5 (-1,-1)  6 (+1,+1)  7 unused
-// grid.x = nb * nb input blocks; block = 64 * min(4, (BS/16)^2) threads; wave w walks the 16 x 16
-// sub-tiles w, w + nwaves, ... of the block, one float4 per lane per sub-tile.  Which neighbours a
-// sub-tile can reach is uniform over the wave, so the edge work is skipped with scalar branches.
+// block = 64 * min(4, (BS/16)^2) threads; wave w walks the 16 x 16 sub-tiles w, w + nwaves, ... of an
+// input block, one float4 per lane per sub-tile.  Which neighbours a sub-tile can reach is uniform
+// over the wave, so the edge work is skipped with scalar branches.  A workgroup takes the input
+// blocks blockIdx.x, blockIdx.x + gridDim.x, ... and requests the scores of its next block before
+// it works on the current one: the grid is a few workgroups per compute unit that each keep two
+// blocks' worth of loads in flight, instead of one short-lived workgroup per block.
 template <int BS>
 __global__ __launch_bounds__(BS >= 32 ? 256 : 64) void conv_pool_kernel(
     const float* __restrict__ A, int L, int p, unsigned long long* __restrict__ pool) {
-    constexpr int NSD = BS / 16, NSUB = NSD * NSD, NW = NSUB < 4 ? NSUB : 4, KSUB = NSUB / NW;
+    // sub-tile of one wave instruction: SH rows x SW columns, 256 scores; rows of 128 bytes (a whole
+    // cache line per row) where the block is wide enough
+    constexpr int SW = BS >= SPION_CONV_SW ? SPION_CONV_SW : 16, SH = 256 / SW;
+    constexpr int NSC = BS / SW, NSUB = (BS / SH) * NSC, NW = NSUB < 4 ? NSUB : 4, KSUB = NSUB / NW;
     const int nb = L / BS;
-    const int I = blockIdx.x / nb, J = blockIdx.x % nb;
+    const int n_blocks = nb * nb;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int lr = lane >> 2, lc = (lane & 3) << 2;
-    const float* base = A + (size_t)I * BS * L + (size_t)J * BS;
+    const int lr = lane / (SW / 4), lc = (lane % (SW / 4)) << 2;
 
-    float4 a4[KSUB];
+    auto load_block = [&](int blk, float4 (&dst)[KSUB]) {
+        const float* base = A + (size_t)(blk / nb) * BS * L + (size_t)(blk % nb) * BS;
 #pragma unroll
-    for (int k = 0; k < KSUB; ++k) {
-        const int st = wave + k * NW;
-        const int u = (st / NSD) * 16 + lr, v0 = (st % NSD) * 16 + lc;
-        a4[k] = *reinterpret_cast<const float4*>(base + (size_t)u * L + v0);
-    }
+        for (int k = 0; k < KSUB; ++k) {
+            const int st = wave + k * NW;
+            const int u = (st / NSC) * SH + lr, v0 = (st % NSC) * SW + lc;
+            dst[k] = *reinterpret_cast<const float4*>(base + (size_t)u * L + v0);
+        }
+    };
+
+    float4 a4[KSUB], nxt[KSUB];
+    if ((int)blockIdx.x < n_blocks) load_block(blockIdx.x, a4);
+    for (int blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
+    const int I = blk / nb, J = blk % nb;
+    const bool more = blk + (int)gridDim.x < n_blocks;
+    if (more) load_block(blk + gridDim.x, nxt);
 
     long long tot[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long s_all = 0;
 #pragma unroll
     for (int k = 0; k < KSUB; ++k) {
         const int st = wave + k * NW;
-        const int su = (st / NSD) * 16, sv = (st % NSD) * 16;
+        const int su = (st / NSC) * SH, sv = (st % NSC) * SW;
         const int u = su + lr, v0 = sv + lc;
-        const bool top = su < p, bottom = su + 15 > BS - 1 - p;
-        const bool left = sv < p, right = sv + 15 > BS - 1 - p;
+        const bool top = su < p, bottom = su + SH - 1 > BS - 1 - p;
+        const bool left = sv < p, right = sv + SW - 1 > BS - 1 - p;
         const int rm_lo = u + 1, rm_hi = p;
         const int r0_lo = (u - BS + 1) > -p ? (u - BS + 1) : -p, r0_hi = u < p ? u : p;
         const int rp_lo = -p, rp_hi = u - BS;
@@ -166,7 +177,14 @@ __global__ __launch_bounds__(BS >= 32 ? 256 : 64) void conv_pool_kernel(
         if (slot < 7 && s != 0 && ti >= 0 && ti < nb && tj >= 0 && tj < nb)
             atomicAdd(&pool[(size_t)ti * nb + tj], (unsigned long long)s);
     }
+    if (more) {
+#pragma unroll
+        for (int k = 0; k < KSUB; ++k) a4[k] = nxt[k];
+    }
+    }   // next input block of this workgroup
 }
+
+constexpr unsigned kConvGrid = 256u * SPION_CONV_WGS_PER_CU;
 
 __global__ void zero_u64_kernel(unsigned long long* __restrict__ p, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -277,7 +295,6 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     if (small)
         for (int i = tid; i < 64 * 128 / 4; i += kFinishThreads) reinterpret_cast<unsigned*>(skew)[i] = 0u;
 
-    SPION_PTP(0);
     // ---- 1. threshold ------------------------------------------------------------------------
     if (mode == 1) {
         // exact k-th smallest (0-based): most-significant-byte-first radix selection.  Up to
@@ -385,7 +402,6 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     }
     __syncthreads();
     const Thresh t = th;
-    SPION_PTP(1);
 
     // ---- 2. per cell: successor bits (which of down / right / diag equal their maximum), the
     //         "above threshold" bit, and the seed flag (first row and first column) ------------------
@@ -405,7 +421,6 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     }
     __syncthreads();
 
-    SPION_PTP(2);
     // ---- 3. fill: every move raises r + c, so anti-diagonal s depends only on s-1 and s-2.  A cell is
     //         reached iff an expanded predecessor lists it as a successor; reached cells are expanded
     //         in turn whether or not they exceed the threshold. -------------------------------------
@@ -461,7 +476,6 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
         }
     }
     __syncthreads();
-    SPION_PTP(3);
     // ---- 4. fl_out = reached and above the threshold, or on the diagonal; kept in expd for step 5 ---
     for (long long i = tid; i < n; i += kFinishThreads) {
         const int r = (int)(i / nb), c = (int)(i % nb);
@@ -474,7 +488,6 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     }
     __syncthreads();
 
-    SPION_PTP(4);
     // ---- 5. compaction: BSR (rows) and BSC (columns); one wave per row / column -------------------
     const bool want_bsc = col_ptr != nullptr;
     for (int r = wave; r < nb; r += kFinishWaves) {
@@ -531,14 +544,12 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     for (int r = wave; r < nb; r += kFinishWaves)
         wave_compact<true>(mask + (long long)r * nb, 1, nb, lane, line_start[r], col_idx, pos,
                            (long long)r * nb, 1, nullptr);
-    SPION_PTP(5);
     if (want_bsc) {
         __syncthreads();   // pos[] of every kept cell is written
         for (int c = wave; c < nb; c += kFinishWaves)
             wave_compact<true>(mask_t + (long long)c * nb, 1, nb, lane, col_start[c], row_idx, pos,
                                (long long)c, nb, bsr_pos);
     }
-    SPION_PTP(6);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -617,12 +628,14 @@ hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* poo
     zero_u64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(
         reinterpret_cast<unsigned long long*>(pool), n);
     unsigned long long* out = reinterpret_cast<unsigned long long*>(pool);
+    // SPION_CONV_WGS_PER_CU workgroups per compute unit (256 of them), each walking several input blocks
+    const unsigned cap = kConvGrid, blocks = (unsigned)n;
     if (bs == 16)
-        conv_pool_kernel<16><<<dim3((unsigned)n), dim3(64), 0, st>>>(A, L, p, out);
+        conv_pool_kernel<16><<<dim3(blocks < 4 * cap ? blocks : 4 * cap), dim3(64), 0, st>>>(A, L, p, out);
     else if (bs == 32)
-        conv_pool_kernel<32><<<dim3((unsigned)n), dim3(256), 0, st>>>(A, L, p, out);
+        conv_pool_kernel<32><<<dim3(blocks < cap ? blocks : cap), dim3(256), 0, st>>>(A, L, p, out);
     else
-        conv_pool_kernel<64><<<dim3((unsigned)n), dim3(256), 0, st>>>(A, L, p, out);
+        conv_pool_kernel<64><<<dim3(blocks < cap ? blocks : cap), dim3(256), 0, st>>>(A, L, p, out);
     return hipGetLastError();
 }
 

@@ -176,4 +176,37 @@ hipError_t launch_frobenius_distance(const float* a, const float* b, size_t n, d
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Traffic yardstick: moves n_tiles x 16 KB from src to dst with the access shapes of the attention
+// kernels (16 bytes per lane from HBM straight into LDS through the memory pipeline, one wave
+// instruction per 1 KB; 16 bytes per lane row stores out).  It reads and writes every byte exactly
+// once, so what the hardware traffic counters report for it gives their scale.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void copy_yardstick_kernel(const char* __restrict__ src, char* __restrict__ dst) {
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    __shared__ __attribute__((aligned(16))) char tile[16384];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const size_t base = (size_t)blockIdx.x * 16384;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int piece = wave * 4 + k;   // 1 KB pieces
+        __builtin_amdgcn_global_load_lds(src + base + piece * 1024 + lane * 16, (lds_ptr)(tile + piece * 1024), 16, 0,
+                                         0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's pieces have landed (it reads only those)
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int off = (wave * 4 + k) * 1024 + lane * 16;
+        *reinterpret_cast<float4*>(dst + base + off) = *reinterpret_cast<const float4*>(tile + off);
+    }
+}
+
+hipError_t launch_copy_yardstick(const void* src, void* dst, size_t n_tiles, hipStream_t st) {
+    copy_yardstick_kernel<<<dim3((unsigned)n_tiles), dim3(256), 0, st>>>(static_cast<const char*>(src),
+                                                                        static_cast<char*>(dst));
+    return hipGetLastError();
+}
+
 }  // namespace spion

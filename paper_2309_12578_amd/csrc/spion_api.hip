@@ -118,14 +118,21 @@ static int pattern_impl(const float* A_s, const spion_pattern_params* p, uint8_t
                         int32_t* col_idx, int32_t* col_ptr, int32_t* row_idx, int32_t* bsr_pos, int32_t* nnzb,
                         int64_t* pool_sum, void* workspace, size_t workspace_bytes, void* hip_stream,
                         bool use_static_scratch) {
-    if (!A_s || !p || !fl_out || !row_ptr || !col_idx || !nnzb) return SPION_ERR_NULL;
+    if (!p) return SPION_ERR_NULL;
+    const uint32_t known_flags = SPION_PATTERN_NO_FILL | SPION_PATTERN_POOL_ONLY | SPION_PATTERN_FROM_POOL;
+    if (p->reserved != 0 || (p->flags & ~known_flags)) return SPION_ERR_PARAM;
+    const bool pool_only = (p->flags & SPION_PATTERN_POOL_ONLY) != 0;
+    const bool from_pool = (p->flags & SPION_PATTERN_FROM_POOL) != 0;
+    if (pool_only && (from_pool || (p->flags & SPION_PATTERN_NO_FILL))) return SPION_ERR_PARAM;
+    if (!from_pool && !A_s) return SPION_ERR_NULL;
+    if ((pool_only || from_pool) && !pool_sum) return SPION_ERR_NULL;
+    if (!pool_only && (!fl_out || !row_ptr || !col_idx || !nnzb)) return SPION_ERR_NULL;
     const bool any_bsc = col_ptr || row_idx || bsr_pos;
     if (any_bsc && !(col_ptr && row_idx && bsr_pos)) return SPION_ERR_NULL;
     if (!shape_ok(p->L, p->block)) return SPION_ERR_SHAPE;
     const int32_t bs = p->block, nb = p->L / bs;
     if (use_static_scratch && nb > SPION_STATIC_MAX_NB) return SPION_ERR_TOO_LARGE;
     if (p->filter < 1 || (p->filter % 2) == 0 || (p->filter - 1) / 2 >= bs) return SPION_ERR_PARAM;
-    if (p->reserved != 0 || (p->flags & ~SPION_PATTERN_NO_FILL)) return SPION_ERR_PARAM;
     const int64_t n = (int64_t)nb * nb;
     int mode = 0;
     long long k_rank = 0;
@@ -167,8 +174,9 @@ static int pattern_impl(const float* A_s, const spion_pattern_params* p, uint8_t
     long long* pool = pool_sum ? reinterpret_cast<long long*>(pool_sum)
                                : reinterpret_cast<long long*>(w + ws.pool_off);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (spion::launch_conv_pool(A_s, p->L, bs, (p->filter - 1) / 2, pool, st) != hipSuccess)
+    if (!from_pool && spion::launch_conv_pool(A_s, p->L, bs, (p->filter - 1) / 2, pool, st) != hipSuccess)
         return SPION_ERR_HIP;
+    if (pool_only) return SPION_OK;
     if (spion::launch_pattern_finish(pool, nb, mode, k_rank, kval, t_abs,
                                      (p->flags & SPION_PATTERN_NO_FILL) ? 1 : 0,
                                      reinterpret_cast<uint8_t*>(w + ws.mask_off),
@@ -216,6 +224,15 @@ int spion_frobenius_distance(const float* A_prev, const float* A_cur, int64_t n,
         return SPION_ERR_WORKSPACE;
     if (spion::launch_frobenius_distance(A_prev, A_cur, (size_t)n, out, workspace,
                                          static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return SPION_ERR_HIP;
+    return SPION_OK;
+}
+
+int spion_copy_yardstick(const void* src, void* dst, size_t n_bytes, void* hip_stream) {
+    if (!src || !dst) return SPION_ERR_NULL;
+    if (n_bytes == 0 || (n_bytes % 16384) != 0 || n_bytes / 16384 > 0x7fffffffull) return SPION_ERR_SHAPE;
+    if (((uintptr_t)src % 16) != 0 || ((uintptr_t)dst % 16) != 0) return SPION_ERR_PARAM;
+    if (spion::launch_copy_yardstick(src, dst, n_bytes / 16384, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return SPION_ERR_HIP;
     return SPION_OK;
 }

@@ -18,6 +18,7 @@ hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long l
 hipError_t launch_index_check(const int* row_ptr, const int* col_idx, const int* col_ptr, const int* row_idx,
                               const int* bsr_pos, int nb, int nnzb, int err_code, int* status, hipStream_t st);
 hipError_t launch_score_mean(const void* A, int is_bf16, int n_maps, size_t n, float* out, hipStream_t st);
+hipError_t launch_copy_yardstick(const void* src, void* dst, size_t n_tiles, hipStream_t st);
 size_t frobenius_workspace_bytes();
 hipError_t launch_frobenius_distance(const float* a, const float* b, size_t n, double* out, void* workspace,
                                      hipStream_t st);
@@ -49,19 +50,18 @@ size_t attn_bwd_workspace_bytes(int BH, int L, int bs, int nb, int nnzb);
 // false when a backward launch for this shape would need more workgroups than a 1-D grid can hold
 bool attn_bwd_grids_fit(int BH, int L, int bs, int nb, int nnzb);
 
-// attn_bf16_kernels.hip: tuned bf16 kernels, BS in {32, 64}
+// attn_bf16_kernels.hip: tuned bf16 forward, BS in {32, 64}
 template <int BS>
 hipError_t fwd_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, void* O, float* LSE,
                     const int* row_ptr, const int* col_idx, hipStream_t st);
+
+// attn_bwd_bf16_kernels.hip: tuned bf16 backward, BS in {32, 64}; both sides in one launch plus the
+// reduction of the partial tiles of split block columns
 template <int BS>
-hipError_t bwd_dq_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
-                       const void* dO, const float* LSE, void* dQ, float* delta, float* lse2, const int* row_ptr,
-                       const int* col_idx, const int* col_ptr, const int* row_idx, int w_max, int split_max,
-                       int4* sched, int4* split, hipStream_t st);
-template <int BS>
-hipError_t bwd_dkv_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* dO,
-                        const float* lse2, const float* delta, void* dK, void* dV, const int* row_idx,
-                        const int4* sched, int w_max, int n_slots, float* partial, hipStream_t st);
+hipError_t bwd_bf16(const AttnShape& s, const void* Q, const void* K, const void* V, const void* O,
+                    const void* dO, const float* LSE, void* dQ, void* dK, void* dV, const int* row_ptr,
+                    const int* col_idx, const int* col_ptr, const int* row_idx, int nnzb, int w_max,
+                    int split_max, int n_slots, float* partial, hipStream_t st);
 
 }  // namespace spion
 #endif

@@ -141,6 +141,59 @@ def test_pattern_variants_no_fill_and_no_conv(sp):
     _check_pattern(sp, A, w.block, 1, si.T_QUANTILE, 0.9, variant="F")
 
 
+def test_pattern_halves_pool_only_then_from_pool(sp):
+    """Eq. 3 + Eq. 4 alone (SPION_PATTERN_POOL_ONLY) and the rest of Algorithm 3 from a given pool_sum
+    (SPION_PATTERN_FROM_POOL).  Conv and pool are linear and the sums exact integers, so the pool_sum
+    maps of two halves of a batch add up to the map of the whole: the way the pattern would be made
+    when the score maps are spread over several GPUs."""
+    w = si.workload(2)
+    Q, K, _, _ = si.make_qkv_do(w, bh_limit=8)
+    A1 = si.make_score_map(w, Q[:4], K[:4]) * np.float32(0.5)
+    A2 = si.make_score_map(w, Q[4:], K[4:]) * np.float32(0.5)
+    nb = w.nb
+    ref1 = oracle.pool_sum(oracle.conv_diag(oracle.quantize(A1), w.filt), w.block)
+    ref2 = oracle.pool_sum(oracle.conv_diag(oracle.quantize(A2), w.filt), w.block)
+    pools = []
+    for A in (A1, A2):
+        ps = torch.full((nb, nb), -1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(sp.spion_pattern_workspace_bytes(w.L, w.block), dtype=torch.uint8, device="cuda")
+        sp.spion_pattern(_dev(A), w.L, w.block, w.filt, w.thresh_mode, w.thresh_value, None, None, None, None,
+                         None, None, None, ps, ws, flags=sp.SPION_PATTERN_POOL_ONLY)
+        pools.append(ps)
+    assert np.array_equal(pools[0].cpu().numpy(), ref1) and np.array_equal(pools[1].cpu().numpy(), ref2)
+    total = pools[0] + pools[1]
+    t = oracle.threshold(ref1 + ref2, w.block, w.thresh_mode, w.thresh_value)
+    ref = oracle.compact(oracle.fill(ref1 + ref2, t))
+    i32 = dict(dtype=torch.int32, device="cuda")
+    fl = torch.empty((nb, nb), dtype=torch.uint8, device="cuda")
+    row_ptr, col_idx, nnzb = torch.empty(nb + 1, **i32), torch.empty(nb * nb, **i32), torch.empty(1, **i32)
+    ws = torch.empty(sp.spion_pattern_workspace_bytes(w.L, w.block), dtype=torch.uint8, device="cuda")
+    keep = total.clone()
+    sp.spion_pattern(None, w.L, w.block, w.filt, w.thresh_mode, w.thresh_value, fl, row_ptr, col_idx, None, None,
+                     None, nnzb, total, ws, flags=sp.SPION_PATTERN_FROM_POOL)
+    n = int(nnzb.item())
+    assert n == ref["nnzb"] and torch.equal(total, keep)                      # pool_sum is read only
+    assert np.array_equal(row_ptr.cpu().numpy(), ref["row_ptr"])
+    assert np.array_equal(col_idx.cpu().numpy()[:n], ref["col_idx"])
+    assert np.array_equal(fl.cpu().numpy(), oracle.fill(ref1 + ref2, t))
+    with pytest.raises(sp.SpionError) as e:                                    # the two flags exclude each other
+        sp.spion_pattern(_dev(A1), w.L, w.block, w.filt, w.thresh_mode, w.thresh_value, fl, row_ptr, col_idx,
+                         None, None, None, nnzb, total, ws,
+                         flags=sp.SPION_PATTERN_FROM_POOL | sp.SPION_PATTERN_POOL_ONLY)
+    assert e.value.code == -5
+
+
+def test_copy_yardstick_moves_every_byte_once(sp):
+    n = 3 * 16384 * 7
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    sp.spion_copy_yardstick(src, dst, n)
+    assert torch.equal(src, dst)
+    with pytest.raises(sp.SpionError) as e:
+        sp.spion_copy_yardstick(src, dst, n - 1)                               # not a multiple of 16 KB
+    assert e.value.code == -2
+
+
 def test_pattern_is_deterministic_across_runs(sp):
     w = si.workload(2)
     Q, K, _, _ = si.make_qkv_do(w, bh_limit=4)
@@ -321,7 +374,7 @@ def test_attention_long_rows_find_their_diagonal(sp):
 
 @pytest.mark.parametrize("dtype,block", [("bf16", 32), ("f32", 16)])
 def test_attention_at_the_largest_block_grid(sp, dtype, block):
-    """nb = 1024 (L = 32768 at block 32, 16384 at block 16): a key block kept by every block row (103 key-side chunks),
+    """nb = 1024 (L = 32768 at block 32, 16384 at block 16): a key block kept by every block row (64 key-side chunks),
     a 120-row column, a 200-block row and a row without its diagonal block.  The dense oracle is out
     of reach at this size, so the check is on sampled outputs: the oracle gives the probabilities of
     one row at a time; O, LSE and dQ of sampled rows and dK, dV of sampled keys follow from them
@@ -402,7 +455,8 @@ def test_attention_at_the_largest_block_grid(sp, dtype, block):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_tall_columns_are_split_into_chunks(sp, dtype):
-    # columns with more kept rows than one key-side work item takes (10): 36, 25, 21 and 11 rows
+    # columns with more kept rows than one key-side work item takes (16): 36, 25, 21 and 17 rows,
+    # next to one with exactly 16
     block, nb, BH, d = 16, 36, 2, 64
     L = nb * block
     rng = np.random.default_rng(11)
@@ -412,9 +466,16 @@ def test_attention_tall_columns_are_split_into_chunks(sp, dtype):
     fl[:, 4] = 1
     fl[:25, 9] = 1
     fl[15:, 15] = 1
-    fl[20:31, 30] = 1
+    fl[14:31, 30] = 1
+    fl[2:17, 33] = 1
     fl[3, :] = 1
     _run_attention_case(sp, Q, K, V, dO, fl, block, dtype)
+    if dtype == "bf16":
+        # the same columns at block 32: the tuned kernels, where every workgroup derives its chunk from
+        # col_ptr and the partial tiles are added by a second launch
+        Q2, K2, V2, dO2 = [si.round_to_dtype(rng.standard_normal((BH, nb * 32, d), dtype=np.float32), dtype)
+                           for _ in range(4)]
+        _run_attention_case(sp, Q2, K2, V2, dO2, fl, 32, dtype)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
