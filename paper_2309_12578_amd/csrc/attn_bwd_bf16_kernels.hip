@@ -277,7 +277,12 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_bf16_kernel(
     const int J = item.J, n = item.ke - item.kb, slot = item.slot;
     const int krow = J * BS + wave * 16 + r;
     const int last = n > 0 ? n - 1 : 0;
-    const int* rows = row_idx + item.kb;
+    // the item's block rows, one per lane (an item has at most kChunk <= 64 of them): read once, so that
+    // no scalar load is in flight inside the steps (scalar loads return out of order, and while one is
+    // outstanding every wait for an LDS read has to wait for all of them)
+    static_assert(kChunk <= 64, "a key-side work item must fit one wave's lanes");
+    const int rows_v = n > 0 ? row_idx[item.kb + (lane < last ? lane : last)] : 0;
+    auto row_at = [&](int t) { return __builtin_amdgcn_readlane(rows_v, t < last ? t : last); };
 
     // six tile loads per wave, plus one 4-byte-per-lane load of LSE in wave 0
     auto issue = [&](bf16_t* qt, bf16_t* dt_, bf16_t* ot, float* lse_s, int I) {
@@ -289,8 +294,8 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_bf16_kernel(
     };
     int Inext = 0;   // block row of step it + 1
     if (n > 0) {
-        issue(ta0, tb0, tc0, lse0, rows[0]);
-        Inext = rows[1 < last ? 1 : last];
+        issue(ta0, tb0, tc0, lse0, row_at(0));
+        Inext = row_at(1);
     }
     // owned K / V fragments (step 0 waits for everything issued up to here)
     bf16x8 kf[2], vf[2];
@@ -312,7 +317,7 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_bf16_kernel(
         // everyone's part of block `it` has landed and the other stage is no longer read
         tiles_ready(false);
         if (it + 1 < n) issue(nq, nd, no, nlse, Inext);
-        Inext = rows[it + 2 < last ? it + 2 : last];
+        Inext = row_at(it + 2);
         // delta of the 16 query rows 16 wave .. + 15: the diagonal of dO O^T; stored negated, it seeds
         // the dP accumulators below.  Wave 0 also turns LSE into log2 units.
         {
@@ -328,28 +333,60 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_bf16_kernel(
             if (wave == 0 && lane < BS) lse_s[lane] *= kLog2e;
         }
         lds_barrier();
-        bf16x4 pq[NT], dsq[NT];
-#pragma unroll
-        for (int qt16 = 0; qt16 < NT; ++qt16) {
-            f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
-            f32x4 dp = *reinterpret_cast<const f32x4*>(&del_s[qt16 * 16 + 4 * g]);   // -delta: the MFMA returns dP - delta
+        // 32 query rows at a time: S and dP of two 16-row tiles, then their share of dV and dK, so that
+        // only two tiles' worth of P and dS are live; LDS operands are requested one MFMA group ahead
+        bf16x8 fq[2], fd[2];
+        auto frags = [&](int qt16) {
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                s = mma_d(s, *reinterpret_cast<const bf16x8*>(qt + qt16 * 16 * kD + sl.frag[c]), kf[c]);     // S = Q K^T
-                dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(dt_ + qt16 * 16 * kD + sl.frag[c]), vf[c]);  // dP = dO V^T
+                fq[c] = *reinterpret_cast<const bf16x8*>(qt + qt16 * 16 * kD + sl.frag[c]);
+                fd[c] = *reinterpret_cast<const bf16x8*>(dt_ + qt16 * 16 * kD + sl.frag[c]);
             }
-            const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&lse_s[qt16 * 16 + 4 * g]);   // log2 units
-            f32x4 p, ds;
+        };
+        auto opnd = [&](int pc, int j) {   // transposed operand of MFMA j of this 32-row group
+            const bf16_t* tile = (j & 1) ? qt : dt_;
+            const int o = sl.tr(j >> 1) + pc * 32 * kD;
+            return join(lds_read_tr(tile + o), lds_read_tr(tile + 16 * kD + o));
+        };
+        frags(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                p[i] = fast_exp2(fmaf(s[i], scale_log2, -lse4[i]));
-                ds[i] = p[i] * dp[i];
+        for (int pc = 0; pc < NT / 2; ++pc) {
+            bf16x4 pq[2], dsq[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int qt16 = 2 * pc + h;
+                f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+                f32x4 dp = *reinterpret_cast<const f32x4*>(&del_s[qt16 * 16 + 4 * g]);   // -delta: the MFMA returns dP - delta
+                const f32x4 lse4 = *reinterpret_cast<const f32x4*>(&lse_s[qt16 * 16 + 4 * g]);   // log2 units
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    s = mma_d(s, fq[c], kf[c]);     // S = Q K^T
+                    dp = mma_d(dp, fd[c], vf[c]);   // dP = dO V^T
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (qt16 + 1 < NT) frags(qt16 + 1);   // lands while the exponentials below run
+                __builtin_amdgcn_sched_barrier(0);
+                f32x4 p, ds;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    p[i] = fast_exp2(fmaf(s[i], scale_log2, -lse4[i]));
+                    ds[i] = p[i] * dp[i];
+                }
+                pq[h] = to_quad<bf16_t>(p);
+                dsq[h] = to_quad<bf16_t>(ds);
             }
-            pq[qt16] = to_quad<bf16_t>(p);
-            dsq[qt16] = to_quad<bf16_t>(ds);
+            // dV^T[d][key] += dO^T P and dK^T[d][key] += Q^T dS for these 32 rows, interleaved
+            const bf16x8 pf = join(pq[0], pq[1]), dsf = join(dsq[0], dsq[1]);
+            bf16x8 ring[2];
+            ring[0] = opnd(pc, 0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (j + 1 < 8) ring[(j + 1) & 1] = opnd(pc, j + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (j & 1) dk[j >> 1] = mma_d(dk[j >> 1], ring[j & 1], dsf);
+                else dv[j >> 1] = mma_d(dv[j >> 1], ring[j & 1], pf);
+            }
         }
-        mma_over_rows_swz<BS>(dv, dt_, pq, sl);    // dV^T[d][key] += dO^T P
-        mma_over_rows_swz<BS>(dk, qt, dsq, sl);    // dK^T[d][key] += Q^T dS
     };
 
     for (int it = 0; it < n; it += 2) {
