@@ -105,18 +105,35 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
             if (it + 1 < n) issue(tgt, Jnext);
             Jnext = col_at(it + 2);
         }
-        // S^T tile kt: [key 16 kt + 4 g + i][query r]
+        // S^T tile kt: [key 16 kt + 4 g + i][query r]; all K fragments are requested up front
+        bf16x8 kfr[NKT][2];
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                kfr[kt][c] = *reinterpret_cast<const bf16x8*>(cur.k + kt * 16 * kD + sl.frag[c]);
         f32x4 s[NKT];
         float mx = -INFINITY;
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
             s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
-                s[kt] = mma_d(s[kt], *reinterpret_cast<const bf16x8*>(cur.k + kt * 16 * kD + sl.frag[c]), qf[c]);
+            for (int c = 0; c < 2; ++c) s[kt] = mma_d(s[kt], kfr[kt][c], qf[c]);
+        }
+        // the transposed V operands of O^T += V^T P^T do not depend on P: requested here, they land
+        // while the maxima and exponentials below are computed
+        constexpr int NM = (BS / 32) * 4;
+        bf16x8 vop[NM];
+#pragma unroll
+        for (int j = 0; j < NM; ++j) {
+            const int o = sl.tr(j & 3) + (j >> 2) * 32 * kD;
+            vop[j] = join(lds_read_tr(cur.v + o), lds_read_tr(cur.v + 16 * kD + o));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[kt][i]);
-        }
         mx = group_max(mx);
         const float m_new = fmaxf(m, mx * scale_log2);
         if (__any(m_new > m)) {   // some row's running maximum moved: rescale what is accumulated
@@ -137,7 +154,11 @@ __global__ __launch_bounds__(BS * 4) void attn_fwd_bf16_kernel(
 #pragma unroll
         for (int pc = 0; pc < BS / 32; ++pc) lacc = mma_d(lacc, ones, join(pq[2 * pc], pq[2 * pc + 1]));
         m = m_new;
-        mma_over_rows_swz<BS>(oacc, cur.v, pq, sl);   // O^T[d][query] += V^T P^T
+#pragma unroll
+        for (int j = 0; j < NM; ++j) {
+            const int pc = j >> 2;
+            oacc[j & 3] = mma_d(oacc[j & 3], vop[j], join(pq[2 * pc], pq[2 * pc + 1]));   // O^T[d][query] += V^T P^T
+        }
     };
 
     for (int it = 0; it < n; it += 2) {
