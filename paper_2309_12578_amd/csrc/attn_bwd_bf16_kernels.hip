@@ -235,23 +235,49 @@ __global__ __launch_bounds__(BS * 4) void attn_bwd_bf16_kernel(
             tiles_ready(it + 1 < n || it == 0);
             if (it + 2 < n) issue(tk, tv, Jnext);
             Jnext = col_at(it + 3);
-            bf16x4 dsq[NT];
+            // all K and V fragments are requested up front; the transposed K operands of the dQ product do
+            // not depend on dS and are requested before the exponentials, so that they land under them
+            bf16x8 kfr[NT][2], vfr[NT][2];
+#pragma unroll
+            for (int kt16 = 0; kt16 < NT; ++kt16)
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    kfr[kt16][c] = *reinterpret_cast<const bf16x8*>(kt + kt16 * 16 * kD + sl.frag[c]);
+                    vfr[kt16][c] = *reinterpret_cast<const bf16x8*>(vt + kt16 * 16 * kD + sl.frag[c]);
+                }
+            f32x4 s[NT], dp[NT];
 #pragma unroll
             for (int kt16 = 0; kt16 < NT; ++kt16) {
                 // dP - delta comes out of the MFMA: the accumulator starts at -delta instead of 0
-                f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f}, dp = f32x4{-delta, -delta, -delta, -delta};
+                s[kt16] = f32x4{0.f, 0.f, 0.f, 0.f};
+                dp[kt16] = f32x4{-delta, -delta, -delta, -delta};
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
-                    const int off = kt16 * 16 * kD + sl.frag[c];
-                    s = mma_d(s, *reinterpret_cast<const bf16x8*>(kt + off), qf[c]);      // S^T = K Q^T
-                    dp = mma_d(dp, *reinterpret_cast<const bf16x8*>(vt + off), dof[c]);   // dP^T = V dO^T
+                    s[kt16] = mma_d(s[kt16], kfr[kt16][c], qf[c]);      // S^T = K Q^T
+                    dp[kt16] = mma_d(dp[kt16], vfr[kt16][c], dof[c]);   // dP^T = V dO^T
                 }
+            }
+            constexpr int NM = (BS / 32) * 4;
+            bf16x8 kop[NM];
+#pragma unroll
+            for (int j = 0; j < NM; ++j) {
+                const int o = sl.tr(j & 3) + (j >> 2) * 32 * kD;
+                kop[j] = join(lds_read_tr(kt + o), lds_read_tr(kt + 16 * kD + o));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x4 dsq[NT];
+#pragma unroll
+            for (int kt16 = 0; kt16 < NT; ++kt16) {
                 f32x4 ds;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ds[i] = fast_exp2(fmaf(s[i], scale_log2, -lse2)) * dp[i];
+                for (int i = 0; i < 4; ++i) ds[i] = fast_exp2(fmaf(s[kt16][i], scale_log2, -lse2)) * dp[kt16][i];
                 dsq[kt16] = to_quad<bf16_t>(ds);
             }
-            mma_over_rows_swz<BS>(dq, kt, dsq, sl);    // dQ^T[d][query] += K^T dS^T
+#pragma unroll
+            for (int j = 0; j < NM; ++j) {
+                const int pc = j >> 2;
+                dq[j & 3] = mma_d(dq[j & 3], kop[j], join(dsq[2 * pc], dsq[2 * pc + 1]));   // dQ^T[d][query] += K^T dS^T
+            }
         };
 
         for (int it = 0; it < n; it += 3) {
