@@ -110,15 +110,15 @@ int spion_pattern(const float *A_s, const spion_pattern_params *p, uint8_t *fl_o
 /*
  * spion_pattern for callers that cannot allocate device memory or carry a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and
- * results as spion_pattern without `workspace` / `workspace_bytes`: the scratch (pooled sums, cell
- * bits, transposed mask, positions) lives in a 1 MiB array that is part of the library's device
+ * results as spion_pattern without `workspace` / `workspace_bytes`: the scratch (per-block partial
+ * sums, pooled sums, cell bits, transposed mask, positions) lives in a 5 MiB array that is part of the library's device
  * image, one copy per GPU, held until the process ends.  The call allocates and frees nothing.
  *   - L / block must not exceed SPION_STATIC_MAX_NB (256; e.g. L = 16384 at block 64), else
  *     SPION_ERR_TOO_LARGE is returned and nothing is enqueued.
  *   - The array's address is looked up on the first call on each device (the device current at the
  *     call, which must be the stream's device); make that first call outside a graph capture.
- *   - All calls on one GPU share the array: the kernels clear what they need at zero themselves, but
- *     two calls that overlap on the same GPU (different streams, or graphs replayed concurrently) race.
+ *   - All calls on one GPU share the array: the kernels overwrite what they use and rely on nothing a
+ *     previous call left there, but two calls that overlap on the same GPU (different streams, or graphs replayed concurrently) race.
  */
 int spion_pattern_static(const float *A_s, const spion_pattern_params *p, uint8_t *fl_out,
                          int32_t *row_ptr, int32_t *col_idx, int32_t *col_ptr, int32_t *row_idx,

@@ -1,14 +1,16 @@
 // Pattern generation kernels for gfx950 (Algorithm 3 and Algorithm 4 of the SPION paper).
 //
-//   conv_pool_kernel      Eq. 3 + Eq. 4 fused: one streaming pass over A^s that scatters every
-//                         (fixed-point) score into the <= 7 pooled blocks its diagonal filter window
-//                         touches.  HBM bound: A^s is read exactly once, nothing L x L is written.
-//   pattern_finish_kernel one workgroup: threshold (exact order statistic / mean + k std),
+//   conv_pool_kernel      Eq. 3 + Eq. 4 fused: one streaming pass over A^s that splits every input
+//                         block's (fixed-point) scores over the <= 7 pooled blocks its diagonal filter
+//                         window touches and writes those seven sums as one record per input block.
+//                         HBM bound: A^s is read exactly once, nothing L x L is written, no atomics.
+//   pattern_finish_kernel one workgroup: adds the records up into pool_sum, then threshold (exact
+//                         order statistic / mean + k std),
 //                         successor bits, anti-diagonal wavefront flood fill, forced diagonal,
 //                         BSR + BSC compaction.  Latency bound (nb^2 <= ~1M cells).
 //
 // Arithmetic: a_q = rint(a * 2^40) as an exact integer; all sums are integer, so any summation
-// order (tiling, atomics) gives the same bits.  This file is compiled with -ffp-contract=off: the
+// order (tiling, partial records) gives the same bits.  This file is compiled with -ffp-contract=off: the
 // fp64 mean / std threshold must round exactly as its sequential definition.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -36,15 +38,10 @@ namespace spion {
 // Fixed point without 64-bit arithmetic in the inner loop: for |a| <= 1, x = a * 2^20 is exact in
 // fp32, hi = floor(x), lo = rint((x - hi) * 2^20) are exact integers of at most 21 bits and
 // a_q = hi * 2^20 + lo == rint(a * 2^40) with ties to even.
-// Build-time tunables of conv_pool_kernel.  Measured at L = 4096, block 64 (cold map): 2 workgroups of
-// 256 threads per compute unit, each walking 8 input blocks, beat both 1 and 3-16 per compute unit
-// (one workgroup per block, the shape without the loop, is 25 % slower); the sub-tile shape (16 x 16,
-// 8 x 32 or 4 x 64 scores per wave instruction) makes no difference.
-#ifndef SPION_CONV_WGS_PER_CU
-#define SPION_CONV_WGS_PER_CU 2
-#endif
-#ifndef SPION_CONV_SW
-#define SPION_CONV_SW 16
+// Build-time tunable of conv_pool_kernel: waves per compute unit (256 of them).  Measured at L = 4096,
+// block 64 (cold map): 8 beat both 4 and 16.
+#ifndef SPION_CONV_WAVES_PER_CU
+#define SPION_CONV_WAVES_PER_CU 8
 #endif
 
 __device__ __forceinline__ int isect(int lo_a, int hi_a, int lo_b, int hi_b) {
@@ -56,139 +53,188 @@ __device__ __forceinline__ int isect(int lo_a, int hi_a, int lo_b, int hi_b) {
 
 __device__ __forceinline__ long long shfl_xor_i64(long long v, int mask) { return __shfl_xor(v, mask); }
 
-// slots: 0 (0,0)  1 (-1,0)  2 (+1,0)  3 (0,-1)  4 (0,+1)  5 (-1,-1)  6 (+1,+1)  7 unused
-// block = 64 * min(4, (BS/16)^2) threads; wave w walks the 16 x 16 sub-tiles w, w + nwaves, ... of an
-// input block, one float4 per lane per sub-tile.  Which neighbours a sub-tile can reach is uniform
-// over the wave, so the edge work is skipped with scalar branches.  A workgroup takes the input
-// blocks blockIdx.x, blockIdx.x + gridDim.x, ... and requests the scores of its next block before
-// it works on the current one: the grid is a few workgroups per compute unit that each keep two
-// blocks' worth of loads in flight, instead of one short-lived workgroup per block.
+// Slot s of the sums of input block (I, J) belongs to pooled block (I + di(s), J + dj(s)):
+// 0 (0,0)  1 (-1,0)  2 (+1,0)  3 (0,-1)  4 (0,+1)  5 (-1,-1)  6 (+1,+1)  7 unused
+__device__ __forceinline__ int slot_di(int s) { return (s == 1 || s == 5) ? -1 : ((s == 2 || s == 6) ? 1 : 0); }
+__device__ __forceinline__ int slot_dj(int s) { return (s == 3 || s == 5) ? -1 : ((s == 4 || s == 6) ? 1 : 0); }
+
+// One wave per input block: the wave walks the block's 16 x 16 sub-tiles (one float4 per lane each) in
+// two halves, and requests the next half (of this block or of its next block) before it works on the
+// current one, so half a block's worth of loads per wave is in flight at all times.  Which neighbours
+// a sub-tile can reach is known per sub-tile, so the edge work is skipped with scalar branches.  The
+// wave's seven slot sums are written, without atomics, into the records of the pooled blocks they
+// belong to: pooled block (ti, tj) owns the 64-byte record part[8 (ti nb + tj) .. + 7], and its slot s is
+// written by exactly one input block, (ti - di(s), tj - dj(s)), if that block exists.  Nothing has to be
+// zeroed beforehand.  Waves take the blocks wave_id, wave_id + n_waves, ...
 template <int BS>
-__global__ __launch_bounds__(BS >= 32 ? 256 : 64) void conv_pool_kernel(
-    const float* __restrict__ A, int L, int p, unsigned long long* __restrict__ pool) {
-    // sub-tile of one wave instruction: SH rows x SW columns, 256 scores; rows of 128 bytes (a whole
-    // cache line per row) where the block is wide enough
-    constexpr int SW = BS >= SPION_CONV_SW ? SPION_CONV_SW : 16, SH = 256 / SW;
-    constexpr int NSC = BS / SW, NSUB = (BS / SH) * NSC, NW = NSUB < 4 ? NSUB : 4, KSUB = NSUB / NW;
+__global__ __launch_bounds__(256, BS == 64 ? 2 : 4) void conv_pool_kernel(const float* __restrict__ A, int L,
+                                                                          int p_arg,
+                                                                          long long* __restrict__ part) {
+    // sub-tile of one wave instruction: SH rows x SW columns, 256 scores
+    constexpr int SW = 16, SH = 256 / SW;
+    constexpr int NSC = BS / SW, NSUB = (BS / SH) * NSC;
+    constexpr int NH = NSUB >= 2 ? 2 : 1, HS = NSUB / NH;   // halves per block, sub-tiles per half
     const int nb = L / BS;
     const int n_blocks = nb * nb;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = gridDim.x * (blockDim.x >> 6);
+    const int first = blockIdx.x * (blockDim.x >> 6) + wave;
     const int lr = lane / (SW / 4), lc = (lane % (SW / 4)) << 2;
 
-    auto load_block = [&](int blk, float4 (&dst)[KSUB]) {
+    auto load_half = [&](int blk, int half, float4 (&dst)[HS]) {
         const float* base = A + (size_t)(blk / nb) * BS * L + (size_t)(blk % nb) * BS;
 #pragma unroll
-        for (int k = 0; k < KSUB; ++k) {
-            const int st = wave + k * NW;
+        for (int k = 0; k < HS; ++k) {
+            const int st = half * HS + k;
             const int u = (st / NSC) * SH + lr, v0 = (st % NSC) * SW + lc;
             dst[k] = *reinterpret_cast<const float4*>(base + (size_t)u * L + v0);
         }
     };
 
-    float4 a4[KSUB], nxt[KSUB];
-    if ((int)blockIdx.x < n_blocks) load_block(blockIdx.x, a4);
-    for (int blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
-    const int I = blk / nb, J = blk % nb;
-    const bool more = blk + (int)gridDim.x < n_blocks;
-    if (more) load_block(blk + gridDim.x, nxt);
-
-    long long tot[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    long long s_all = 0;
+    long long tot[8];
+    long long s_all;
+    // sub-tiles [half * HS, half * HS + HS) of the current block, scores in src
+    auto work_half = [&](int half, const float4 (&src)[HS]) {
+        // The edge weights and the coordinates they are made from depend only on the lane, the sub-tile
+        // and the filter, not on the block; left to itself the compiler computes all of them once and
+        // keeps several hundred values in registers (and in scratch memory) across the loop.  Hiding
+        // the filter's half-width and the lane's coordinates here makes them per-sub-tile work.
 #pragma unroll
-    for (int k = 0; k < KSUB; ++k) {
-        const int st = wave + k * NW;
-        const int su = (st / NSC) * SH, sv = (st % NSC) * SW;
-        const int u = su + lr, v0 = sv + lc;
-        const bool top = su < p, bottom = su + SH - 1 > BS - 1 - p;
-        const bool left = sv < p, right = sv + SW - 1 > BS - 1 - p;
-        const int rm_lo = u + 1, rm_hi = p;
-        const int r0_lo = (u - BS + 1) > -p ? (u - BS + 1) : -p, r0_hi = u < p ? u : p;
-        const int rp_lo = -p, rp_hi = u - BS;
-        const float av[4] = {a4[k].x, a4[k].y, a4[k].z, a4[k].w};
-        int hi[4], lo[4], c0_lo[4], c0_hi[4];
-        int s_hi = 0, s_lo = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int v = v0 + e;
-            const float x = av[e] * 1048576.0f;
-            const float xf = floorf(x);
-            hi[e] = (int)xf;
-            lo[e] = (int)rintf((x - xf) * 1048576.0f);
-            s_hi += hi[e];
-            s_lo += lo[e];
-            c0_lo[e] = (v - BS + 1) > -p ? (v - BS + 1) : -p;
-            c0_hi[e] = v < p ? v : p;
-        }
-        s_all += ((long long)s_hi << 20) + s_lo;
-        // weights < 128 and |hi|, lo <= 2^20: 24-bit multiplies, 4 terms fit 32 bits
-        auto edge = [&](int slot, auto weight) {
-            int n_hi = 0, n_lo = 0;
+        for (int k = 0; k < HS; ++k) {
+            int p = p_arg, lrow = lr, lcol = lc;
+            asm volatile("" : "+s"(p), "+v"(lrow), "+v"(lcol));
+            __builtin_amdgcn_sched_barrier(0);   // one sub-tile at a time: their temporaries do not pile up
+            const int st = half * HS + k;
+            const int su = (st / NSC) * SH, sv = (st % NSC) * SW;
+            const int u = su + lrow, v0 = sv + lcol;
+            const bool top = su < p, bottom = su + SH - 1 > BS - 1 - p;
+            const bool left = sv < p, right = sv + SW - 1 > BS - 1 - p;
+            const int rm_lo = u + 1, rm_hi = p;
+            const int r0_lo = (u - BS + 1) > -p ? (u - BS + 1) : -p, r0_hi = u < p ? u : p;
+            const int rp_lo = -p, rp_hi = u - BS;
+            const float av[4] = {src[k].x, src[k].y, src[k].z, src[k].w};
+            int hi[4], lo[4], c0_lo[4], c0_hi[4];
+            int s_hi = 0, s_lo = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int w = weight(e);
-                n_hi += __mul24(w, hi[e]);
-                n_lo += __mul24(w, lo[e]);
+                const int v = v0 + e;
+                const float x = av[e] * 1048576.0f;
+                const float xf = floorf(x);
+                hi[e] = (int)xf;
+                lo[e] = (int)rintf((x - xf) * 1048576.0f);
+                s_hi += hi[e];
+                s_lo += lo[e];
+                c0_lo[e] = (v - BS + 1) > -p ? (v - BS + 1) : -p;
+                c0_hi[e] = v < p ? v : p;
             }
-            tot[slot] += ((long long)n_hi << 20) + n_lo;
-        };
-        if (top) edge(1, [&](int e) { return isect(rm_lo, rm_hi, c0_lo[e], c0_hi[e]); });
-        if (bottom) edge(2, [&](int e) { return isect(rp_lo, rp_hi, c0_lo[e], c0_hi[e]); });
-        if (left) edge(3, [&](int e) { return isect(r0_lo, r0_hi, v0 + e + 1, p); });
-        if (right) edge(4, [&](int e) { return isect(r0_lo, r0_hi, -p, v0 + e - BS); });
-        if (top && left) edge(5, [&](int e) { return isect(rm_lo, rm_hi, v0 + e + 1, p); });
-        if (bottom && right) edge(6, [&](int e) { return isect(rp_lo, rp_hi, -p, v0 + e - BS); });
-    }
-    long long others = 0;
+            s_all += ((long long)s_hi << 20) + s_lo;
+            // weights < 128 and |hi|, lo <= 2^20: 24-bit multiplies, 4 terms fit 32 bits
+            auto edge = [&](int slot, auto weight) {
+                int n_hi = 0, n_lo = 0;
 #pragma unroll
-    for (int t = 1; t < 7; ++t) others += tot[t];
-    tot[0] = (long long)(2 * p + 1) * s_all - others;
+                for (int e = 0; e < 4; ++e) {
+                    const int w = weight(e);
+                    n_hi += __mul24(w, hi[e]);
+                    n_lo += __mul24(w, lo[e]);
+                }
+                tot[slot] += ((long long)n_hi << 20) + n_lo;
+            };
+            if (top) edge(1, [&](int e) { return isect(rm_lo, rm_hi, c0_lo[e], c0_hi[e]); });
+            if (bottom) edge(2, [&](int e) { return isect(rp_lo, rp_hi, c0_lo[e], c0_hi[e]); });
+            if (left) edge(3, [&](int e) { return isect(r0_lo, r0_hi, v0 + e + 1, p); });
+            if (right) edge(4, [&](int e) { return isect(r0_lo, r0_hi, -p, v0 + e - BS); });
+            if (top && left) edge(5, [&](int e) { return isect(rm_lo, rm_hi, v0 + e + 1, p); });
+            if (bottom && right) edge(6, [&](int e) { return isect(rp_lo, rp_hi, -p, v0 + e - BS); });
+        }
+    };
 
-    // reduce-scatter butterfly over the wave: 8 slots -> 4 -> 2 -> 1, then 3 plain steps
+    float4 a[HS], b[HS];
+    if (first < n_blocks) load_half(first, 0, a);
+    for (int blk = first; blk < n_blocks; blk += n_waves) {
+        const bool more = blk + n_waves < n_blocks;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const bool up = lane & 32;
-        const long long send = up ? tot[k] : tot[k + 4];
-        const long long keep = up ? tot[k + 4] : tot[k];
-        tot[k] = keep + shfl_xor_i64(send, 32);
-    }
+        for (int t = 0; t < 8; ++t) tot[t] = 0;
+        s_all = 0;
+        if constexpr (NH == 2) {
+            load_half(blk, 1, b);
+            work_half(0, a);
+            if (more) load_half(blk + n_waves, 0, a);
+            work_half(1, b);
+        } else {
+            if (more) load_half(blk + n_waves, 0, b);
+            work_half(0, a);
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const bool up = lane & 16;
-        const long long send = up ? tot[k] : tot[k + 2];
-        const long long keep = up ? tot[k + 2] : tot[k];
-        tot[k] = keep + shfl_xor_i64(send, 16);
-    }
-    {
-        const bool up = lane & 8;
-        const long long send = up ? tot[0] : tot[1];
-        const long long keep = up ? tot[1] : tot[0];
-        tot[0] = keep + shfl_xor_i64(send, 8);
-    }
-    long long s = tot[0];
-    s += shfl_xor_i64(s, 4);
-    s += shfl_xor_i64(s, 2);
-    s += shfl_xor_i64(s, 1);
-    if ((lane & 7) == 0) {
-        const int slot = ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
-        const int di_tab[8] = {0, -1, 1, 0, 0, -1, 1, 0};
-        const int dj_tab[8] = {0, 0, 0, -1, 1, -1, 1, 0};
-        const int ti = I + di_tab[slot], tj = J + dj_tab[slot];
-        if (slot < 7 && s != 0 && ti >= 0 && ti < nb && tj >= 0 && tj < nb)
-            atomicAdd(&pool[(size_t)ti * nb + tj], (unsigned long long)s);
-    }
-    if (more) {
+            for (int k = 0; k < HS; ++k) a[k] = b[k];
+        }
+        long long others = 0;
 #pragma unroll
-        for (int k = 0; k < KSUB; ++k) a4[k] = nxt[k];
+        for (int t = 1; t < 7; ++t) others += tot[t];
+        tot[0] = (long long)(2 * p_arg + 1) * s_all - others;
+
+        // reduce-scatter butterfly over the wave: 8 slots -> 4 -> 2 -> 1, then 3 plain steps
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool up = lane & 32;
+            const long long send = up ? tot[k] : tot[k + 4];
+            const long long keep = up ? tot[k + 4] : tot[k];
+            tot[k] = keep + shfl_xor_i64(send, 32);
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const bool up = lane & 16;
+            const long long send = up ? tot[k] : tot[k + 2];
+            const long long keep = up ? tot[k + 2] : tot[k];
+            tot[k] = keep + shfl_xor_i64(send, 16);
+        }
+        {
+            const bool up = lane & 8;
+            const long long send = up ? tot[0] : tot[1];
+            const long long keep = up ? tot[1] : tot[0];
+            tot[0] = keep + shfl_xor_i64(send, 8);
+        }
+        long long s = tot[0];
+        s += shfl_xor_i64(s, 4);
+        s += shfl_xor_i64(s, 2);
+        s += shfl_xor_i64(s, 1);
+        if ((lane & 7) == 0) {
+            const int slot = ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
+            const int ti = blk / nb + slot_di(slot), tj = blk % nb + slot_dj(slot);
+            if (slot < 7 && ti >= 0 && ti < nb && tj >= 0 && tj < nb) part[((size_t)ti * nb + tj) * 8 + slot] = s;
+        }
     }
-    }   // next input block of this workgroup
 }
 
-constexpr unsigned kConvGrid = 256u * SPION_CONV_WGS_PER_CU;
+// pool_sum of cell (ti, tj): the sum of the slots of its record whose source block exists (the
+// other slots were never written).
+struct PoolRecord {
+    uint4 q[4];
+};
+__device__ __forceinline__ PoolRecord load_record(const long long* __restrict__ part, size_t cell) {
+    PoolRecord rec;
+    const uint4* src = reinterpret_cast<const uint4*>(part + cell * 8);
+#pragma unroll
+    for (int h = 0; h < 4; ++h) rec.q[h] = src[h];
+    return rec;
+}
+__device__ __forceinline__ long long sum_record(const PoolRecord& rec, int nb, int ti, int tj) {
+    long long acc = 0;
+#pragma unroll
+    for (int s = 0; s < 7; ++s) {
+        const uint4 q = rec.q[s >> 1];
+        const unsigned long long v = (s & 1) ? ((unsigned long long)q.w << 32 | q.z) : ((unsigned long long)q.y << 32 | q.x);
+        const int si = ti - slot_di(s), sj = tj - slot_dj(s);
+        const bool ok = si >= 0 && si < nb && sj >= 0 && sj < nb;
+        acc += ok ? (long long)v : 0ll;
+    }
+    return acc;
+}
 
-__global__ void zero_u64_kernel(unsigned long long* __restrict__ p, size_t n) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0ull;
+// pool_sum alone (the convolution + pooling stage run on its own)
+__global__ __launch_bounds__(256) void pool_gather_kernel(const long long* __restrict__ part, int nb,
+                                                          long long* __restrict__ pool) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < nb * nb) pool[i] = sum_record(load_record(part, (size_t)i), nb, i / nb, i % nb);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -216,6 +262,23 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
         const int o = __shfl_up(v, off);
         if (lane >= off) v += o;
     }
+    return v;
+}
+
+// The same scan with DPP moves (VALU speed, no LDS crossbar): shifts of 1, 2, 4, 8 inside each row of
+// 16 lanes, then lane 15 of rows 0 and 2 added to rows 1 and 3, then lane 31 added to rows 2 and 3.
+// A lane whose source is outside its row, or whose row is masked off, adds the 0 given as old value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_fetch(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ int wave_inclusive_scan_dpp(int v) {
+    v += dpp_fetch<0x111, 0xf>(v);   // row_shr:1
+    v += dpp_fetch<0x112, 0xf>(v);   // row_shr:2
+    v += dpp_fetch<0x114, 0xf>(v);   // row_shr:4
+    v += dpp_fetch<0x118, 0xf>(v);   // row_shr:8
+    v += dpp_fetch<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_fetch<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
     return v;
 }
 
@@ -263,12 +326,22 @@ __device__ __forceinline__ int wave_compact(const uint8_t* f, int stride, int nb
     return offset - start;
 }
 
+// Radix selection: digits of kDigitBits bits, most significant first; 64-bit keys need kSelPasses.
+constexpr int kDigitBits = 11, kBins = 1 << kDigitBits, kSelPasses = 6;
+static_assert(kDigitBits * (kSelPasses - 1) < 64 && kDigitBits * kSelPasses >= 64, "passes must cover 64 bits");
+static_assert(kBins == 32 * 64, "one wave scans a histogram with 32 bins per lane");
+// Where the counter of digit D lives in a histogram: lane D / 32 of a scanning wave owns the 32
+// consecutive digits 32 (D / 32) .. + 31 as eight 16-byte groups, and group j of all lanes is
+// contiguous, so that the wave reads it without bank conflicts.
+__device__ __forceinline__ int bin_slot(unsigned D) { return (int)(((D >> 2) & 7u) * 256u + (D >> 5) * 4u + (D & 3u)); }
+
 // mode: 0 = threshold given in t_abs, 1 = quantile rank k_rank, 2 = mean + kval * std.
+// part: partial records of conv_pool_kernel, from which pool[] is first computed; nullptr: pool[] is given.
 // mask_g / expd_g / pos: scratch arrays of nb*nb entries in global memory; when use_lds is set the
 // byte arrays live in dynamic LDS instead (3 * nb * nb bytes).  mask_g holds 2 * nb * nb bytes.
 __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
-    const long long* __restrict__ pool, int nb, int mode, long long k_rank, double kval, double t_abs,
-    int no_fill, int use_lds, uint8_t* mask_g, uint8_t* expd_g, int* pos,
+    const long long* __restrict__ part, long long* pool, int nb, int mode, int k_rank, double kval,
+    double t_abs, int no_fill, int use_lds, uint8_t* mask_g, uint8_t* expd_g, int* pos,
     uint8_t* __restrict__ fl, int* __restrict__ row_ptr, int* __restrict__ col_idx,
     int* __restrict__ col_ptr, int* __restrict__ row_idx, int* __restrict__ bsr_pos,
     int* __restrict__ nnzb_out) {
@@ -279,99 +352,144 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     uint8_t* expd = use_lds ? dyn_lds + n : expd_g;
     uint8_t* mask_t = use_lds ? dyn_lds + 2 * n : mask_g + n;   // final mask, transposed (step 5)
     if (use_lds > 1) pos = reinterpret_cast<int*>(dyn_lds + 4 * n);   // 3n rounded up to a multiple of 4
-    __shared__ unsigned hist[256];
-    __shared__ Thresh th;
-    __shared__ unsigned long long sel_prefix;
-    __shared__ long long sel_k;
-    __shared__ int scan_scratch[kFinishWaves + 1];
-    __shared__ int line_start[SPION_MAX_NB_INTERNAL];
-    __shared__ int col_start[SPION_MAX_NB_INTERNAL];
+    // One block of LDS, used twice: three histograms while the quantile is selected; afterwards the
+    // arrays of the fill and the compaction.
+    __shared__ __attribute__((aligned(16))) unsigned char sh[3 * kBins * 4];
+    unsigned* const hist = reinterpret_cast<unsigned*>(sh);
     // nb <= 64 only: successor bits of row r in anti-diagonal order, skew[r][s] = bits of cell
-    // (r, s - r), zero where s - r is outside the row; and the "reached" bit of every cell as one
-    // 128-bit mask per row in the same order
-    __shared__ __attribute__((aligned(16))) uint8_t skew[64 * 128];
-    __shared__ unsigned rbits[64 * 4];
+    // (r, s - r), zero where s - r is outside the row; the "reached" bit of every cell as one 128-bit
+    // mask per row in the same order; the final mask as one 64-bit word per row and per column
+    uint8_t* const skew = sh;                                                   // 64 * 128
+    int* const line_start = reinterpret_cast<int*>(sh + 8192);                  // SPION_MAX_NB ints
+    int* const col_start = reinterpret_cast<int*>(sh + 12288);                  // SPION_MAX_NB ints
+    unsigned* const rbits = reinterpret_cast<unsigned*>(sh + 16384);            // 64 * 4
+    unsigned long long* const rowmask = reinterpret_cast<unsigned long long*>(sh + 17408);   // 64
+    unsigned long long* const colmask = reinterpret_cast<unsigned long long*>(sh + 17920);   // 64
+    static_assert(17920 + 512 <= 3 * kBins * 4 && SPION_MAX_NB_INTERNAL * 4 == 4096, "LDS carving");
+    __shared__ Thresh th;
+    __shared__ int scan_scratch[kFinishWaves + 1];
     const bool small = nb <= 64;
-    if (small)
-        for (int i = tid; i < 64 * 128 / 4; i += kFinishThreads) reinterpret_cast<unsigned*>(skew)[i] = 0u;
 
-    // ---- 1. threshold ------------------------------------------------------------------------
-    if (mode == 1) {
-        // exact k-th smallest (0-based): most-significant-byte-first radix selection.  Up to
-        // kCached values per thread stay in registers across the 8 passes (covers nb <= 64).
-        constexpr int kCached = 4;
-        const bool cached = n <= (long long)kCached * kFinishThreads;
-        unsigned long long key[kCached];
+    // ---- 0. pool_sum from the partial records; up to kCached cells per thread stay in registers ----
+    constexpr int kCached = 4;
+    const bool cached = n <= (long long)kCached * kFinishThreads;
+    long long val[kCached] = {0, 0, 0, 0};
+    if (part) {
+        for (long long base = 0; base < n; base += (long long)kCached * kFinishThreads) {
+            // all records of this round are requested before the first is used
+            PoolRecord rec[kCached];
+#pragma unroll
+            for (int j = 0; j < kCached; ++j) {
+                const long long i = base + (long long)j * kFinishThreads + tid;
+                rec[j] = load_record(part, (size_t)(i < n ? i : n - 1));
+            }
+#pragma unroll
+            for (int j = 0; j < kCached; ++j) {
+                const long long i = base + (long long)j * kFinishThreads + tid;
+                if (i < n) {
+                    const long long v = sum_record(rec[j], nb, (int)(i / nb), (int)(i % nb));
+                    pool[i] = v;
+                    val[j] = v;
+                }
+            }
+        }
+        __syncthreads();   // pool[] is read by other threads from here on
+    } else if (cached) {
 #pragma unroll
         for (int j = 0; j < kCached; ++j) {
             const long long i = (long long)j * kFinishThreads + tid;
-            key[j] = (cached && i < n) ? ((unsigned long long)pool[i] ^ 0x8000000000000000ull) : 0ull;
+            if (i < n) val[j] = pool[i];
         }
-        if (tid == 0) {
-            sel_prefix = 0ull;
-            sel_k = k_rank;
+    }
+
+    // ---- 1. threshold ------------------------------------------------------------------------
+    if (mode == 1) {
+        // Exact k-th smallest (0-based) by radix selection on key = value with the sign bit flipped.
+        // One barrier per pass: after it every wave scans the histogram itself (32 bins per lane)
+        // and derives the same digit, so nothing is broadcast through LDS; three histograms rotate,
+        // the one of the pass before is cleared while the current one is scanned.
+        for (int i = tid; i < 3 * kBins; i += kFinishThreads) hist[i] = 0u;
+        unsigned long long key[kCached];
+        bool alive[kCached];   // still equal to the selected prefix
+#pragma unroll
+        for (int j = 0; j < kCached; ++j) {
+            key[j] = (unsigned long long)val[j] ^ 0x8000000000000000ull;
+            alive[j] = cached && (long long)j * kFinishThreads + tid < n;
         }
-        if (tid < 256) hist[tid] = 0u;
         __syncthreads();
-        auto count = [&](unsigned long long u, bool in_range, int pass, unsigned long long prefix) {
-            const int shift = pass * 8;
-            const bool match = in_range && ((pass == 7) || ((u >> (shift + 8)) == (prefix >> (shift + 8))));
-            const unsigned byte = (unsigned)((u >> shift) & 0xFFull);
-            // the leading bytes are usually equal for the whole wave: one atomic instead of 64
-            const unsigned long long m = __ballot(match);
-            if (m == 0ull) return;
-            const unsigned first = __shfl(byte, __ffsll((long long)m) - 1);
-            if (__ballot(match && byte == first) == m) {
-                if (lane == 0) atomicAdd(&hist[first], (unsigned)__popcll(m));
-            } else if (match) {
-                atomicAdd(&hist[byte], 1u);
-            }
-        };
-        for (int pass = 7; pass >= 0; --pass) {
-            const int shift = pass * 8;
-            const unsigned long long prefix = sel_prefix;
-            const long long k = sel_k;
+        unsigned long long prefix = 0ull;
+        int k = k_rank;
+#pragma unroll 1
+        for (int pass = 0; pass < kSelPasses; ++pass) {
+            const int shift = kDigitBits * (kSelPasses - 1 - pass);   // 55, 44, ..., 0
+            const int top = shift + kDigitBits;                       // bits >= top are already decided
+            unsigned* const h = hist + (pass % 3) * kBins;
+            auto count = [&](unsigned long long u, bool match) {
+                const unsigned digit = (unsigned)(u >> shift) & (unsigned)(kBins - 1);
+                // the leading digits are usually equal for the whole wave: one atomic instead of 64
+                const unsigned long long m = __ballot(match);
+                if (m == 0ull) return;
+                const unsigned first = (unsigned)__builtin_amdgcn_readlane((int)digit, __ffsll((long long)m) - 1);
+                if (__ballot(match && digit == first) == m) {
+                    if (lane == 0) atomicAdd(&h[bin_slot(first)], (unsigned)__popcll(m));
+                } else if (match) {
+                    atomicAdd(&h[bin_slot(digit)], 1u);
+                }
+            };
             if (cached) {
 #pragma unroll
-                for (int j = 0; j < kCached; ++j)
-                    count(key[j], (long long)j * kFinishThreads + tid < n, pass, prefix);
+                for (int j = 0; j < kCached; ++j) count(key[j], alive[j]);
             } else {
                 for (long long base = 0; base < n; base += kFinishThreads) {
                     const long long i = base + tid;
                     const unsigned long long u =
                         i < n ? ((unsigned long long)pool[i] ^ 0x8000000000000000ull) : 0ull;
-                    count(u, i < n, pass, prefix);
+                    count(u, i < n && (top >= 64 || (u >> top) == (prefix >> top)));
                 }
             }
             __syncthreads();
-            // wave 0 finds the bin b with excl(b) <= k < incl(b); 4 bins per lane
-            if (wave == 0) {
-                unsigned c[4];
-                int s4 = 0;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    c[q] = hist[4 * lane + q];
-                    s4 += (int)c[q];
-                }
-                const int incl = wave_inclusive_scan(s4, lane);
-                long long e = incl - s4;
-                if (k >= e && k < incl) {
-                    int q = 0;
-                    while (k >= e + (long long)c[q]) {
-                        e += c[q];
-                        ++q;
-                    }
-                    sel_k = k - e;
-                    sel_prefix = prefix | ((unsigned long long)(4 * lane + q) << shift);
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) hist[4 * lane + q] = 0u;
+            {
+                unsigned* const hz = hist + ((pass + 2) % 3) * kBins;   // last read before the barrier above
+                for (int i = tid; i < kBins; i += kFinishThreads) hz[i] = 0u;
             }
-            __syncthreads();
+            // the digit whose bin holds rank k: lane owns digits 32 lane .. 32 lane + 31 as 8 groups of 4
+            const uint4* const h4 = reinterpret_cast<const uint4*>(h);
+            int s4[8], s32 = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint4 v = h4[j * 64 + lane];
+                s4[j] = (int)(v.x + v.y + v.z + v.w);
+                s32 += s4[j];
+            }
+            const int incl = wave_inclusive_scan_dpp(s32);
+            int e = incl - s32, qj = 0;
+            const bool hit = k >= e && k < incl;   // exactly one lane: the matching keys number more than k
+#pragma unroll
+            for (int j = 0; j < 7; ++j) {
+                const bool adv = qj == j && k >= e + s4[j];
+                e = adv ? e + s4[j] : e;
+                qj = adv ? j + 1 : qj;
+            }
+            const uint4 v = h4[qj * 64 + lane];
+            const int c3[3] = {(int)v.x, (int)v.y, (int)v.z};
+            int qt = 0;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const bool adv = qt == j && k >= e + c3[j];
+                e = adv ? e + c3[j] : e;
+                qt = adv ? j + 1 : qt;
+            }
+            const int src = __ffsll((long long)__ballot(hit)) - 1;
+            const unsigned digit = (unsigned)__builtin_amdgcn_readlane(32 * lane + 4 * qj + qt, src);
+            k -= __builtin_amdgcn_readlane(e, src);
+            prefix |= (unsigned long long)digit << shift;
+#pragma unroll
+            for (int j = 0; j < kCached; ++j)
+                alive[j] = alive[j] && ((unsigned)(key[j] >> shift) & (unsigned)(kBins - 1)) == digit;
         }
         if (tid == 0) {
             th.is_int = 1;
-            th.ti = (long long)(sel_prefix ^ 0x8000000000000000ull);
+            th.ti = (long long)(prefix ^ 0x8000000000000000ull);
             th.td = (double)th.ti;
         }
     } else if (mode == 2) {
@@ -402,22 +520,32 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     }
     __syncthreads();
     const Thresh t = th;
+    if (small) {
+        // the histograms are done with: their LDS now holds the arrays of the steps below
+        for (int i = tid; i < 64 * 128 / 4; i += kFinishThreads) reinterpret_cast<unsigned*>(skew)[i] = 0u;
+        __syncthreads();
+    }
 
     // ---- 2. per cell: successor bits (which of down / right / diag equal their maximum), the
     //         "above threshold" bit, and the seed flag (first row and first column) ------------------
-    for (long long i = tid; i < n; i += kFinishThreads) {
-        const int r = (int)(i / nb), c = (int)(i % nb);
-        const long long x = pool[i];
-        unsigned m = above(x, t) ? kAbove : 0u;
-        if (r + 1 < nb && c + 1 < nb) {
-            const long long dn = pool[i + nb], rt = pool[i + 1], dg = pool[i + nb + 1];
-            long long mx = dn > rt ? dn : rt;
-            mx = mx > dg ? mx : dg;
-            m |= (dn == mx ? kDown : 0u) | (rt == mx ? kRight : 0u) | (dg == mx ? kDiag : 0u);
+    for (long long base = 0; base < n; base += (long long)kCached * kFinishThreads) {
+#pragma unroll
+        for (int j = 0; j < kCached; ++j) {
+            const long long i = base + (long long)j * kFinishThreads + tid;
+            if (i >= n) continue;
+            const int r = (int)(i / nb), c = (int)(i % nb);
+            const long long x = cached ? val[j] : pool[i];
+            unsigned m = above(x, t) ? kAbove : 0u;
+            if (r + 1 < nb && c + 1 < nb) {
+                const long long dn = pool[i + nb], rt = pool[i + 1], dg = pool[i + nb + 1];
+                long long mx = dn > rt ? dn : rt;
+                mx = mx > dg ? mx : dg;
+                m |= (dn == mx ? kDown : 0u) | (rt == mx ? kRight : 0u) | (dg == mx ? kDiag : 0u);
+            }
+            mask[i] = (uint8_t)m;
+            if (small) skew[r * 128 + r + c] = (uint8_t)(m & 7u);
+            else expd[i] = no_fill ? (uint8_t)kReached : ((r == 0 || c == 0) ? (uint8_t)kExpanded : (uint8_t)0);
         }
-        mask[i] = (uint8_t)m;
-        if (small) skew[r * 128 + r + c] = (uint8_t)(m & 7u);
-        expd[i] = no_fill ? (uint8_t)kReached : ((r == 0 || c == 0) ? (uint8_t)kExpanded : (uint8_t)0);
     }
     __syncthreads();
 
@@ -476,11 +604,68 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
         }
     }
     __syncthreads();
+    const bool want_bsc = col_ptr != nullptr;
+
+    if (small) {
+        // ---- 4 + 5, nb <= 64: the final mask as one 64-bit word per row (a wave's ballot over the
+        //      row's cells) and per column; every kept cell then finds its place in BSR and BSC from
+        //      population counts of those words, with no pass over the matrix in between -------------
+        auto kept = [&](int r, int c) {
+            if (c >= nb) return false;
+            const bool reached = no_fill || ((rbits[r * 4 + ((r + c) >> 5)] >> ((r + c) & 31)) & 1u) != 0u;
+            return (reached && (mask[r * nb + c] & kAbove)) || r == c;
+        };
+        for (int r = wave; r < nb; r += kFinishWaves) {
+            const bool f = kept(r, lane);
+            if (lane < nb) fl[r * nb + lane] = f ? 1 : 0;
+            const unsigned long long m = __ballot(f);
+            if (lane == 0) rowmask[r] = m;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const int v = lane < nb ? __popcll(rowmask[lane]) : 0;
+            const int incl = wave_inclusive_scan(v, lane);
+            if (lane < nb) {
+                line_start[lane] = incl - v;
+                row_ptr[lane] = incl - v;
+            }
+            if (lane == 63) {
+                row_ptr[nb] = incl;
+                *nnzb_out = incl;
+            }
+        } else if (wave == 1 && want_bsc) {
+            unsigned long long cm = 0ull;
+            for (int r = 0; r < nb; ++r) cm |= ((rowmask[r] >> lane) & 1ull) << r;
+            if (lane < nb) colmask[lane] = cm;
+            const int v = lane < nb ? __popcll(cm) : 0;
+            const int incl = wave_inclusive_scan(v, lane);
+            if (lane < nb) {
+                col_start[lane] = incl - v;
+                col_ptr[lane] = incl - v;
+            }
+            if (lane == 63) col_ptr[nb] = incl;
+        }
+        __syncthreads();
+        for (int r = wave; r < nb; r += kFinishWaves) {
+            const int c = lane;
+            const unsigned long long rm = rowmask[r];
+            if (c < nb && ((rm >> c) & 1ull)) {
+                const int k = line_start[r] + __popcll(rm & ((1ull << c) - 1ull));
+                col_idx[k] = c;
+                if (want_bsc) {
+                    const int k2 = col_start[c] + __popcll(colmask[c] & ((1ull << r) - 1ull));
+                    row_idx[k2] = r;
+                    bsr_pos[k2] = k;
+                }
+            }
+        }
+        return;
+    }
+
     // ---- 4. fl_out = reached and above the threshold, or on the diagonal; kept in expd for step 5 ---
     for (long long i = tid; i < n; i += kFinishThreads) {
         const int r = (int)(i / nb), c = (int)(i % nb);
-        const bool reached = (small && !no_fill) ? ((rbits[r * 4 + ((r + c) >> 5)] >> ((r + c) & 31)) & 1u) != 0u
-                                                 : (expd[i] & kReached) != 0;
+        const bool reached = (expd[i] & kReached) != 0;
         const uint8_t f = ((reached && (mask[i] & kAbove)) || r == c) ? 1 : 0;
         fl[i] = f;
         mask[i] = f;
@@ -489,7 +674,6 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     __syncthreads();
 
     // ---- 5. compaction: BSR (rows) and BSC (columns); one wave per row / column -------------------
-    const bool want_bsc = col_ptr != nullptr;
     for (int r = wave; r < nb; r += kFinishWaves) {
         const int k = wave_compact<false>(mask + (long long)r * nb, 1, nb, lane, 0, nullptr, nullptr, 0, 0,
                                           nullptr);
@@ -501,24 +685,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
         }
     }
     __syncthreads();
-    if (small) {
-        // nb <= 64: one wave scans the row counts, another the column counts
-        if (wave < 2 && (wave == 0 || want_bsc)) {
-            int* start = wave == 0 ? line_start : col_start;
-            int* ptr = wave == 0 ? row_ptr : col_ptr;
-            const int v = lane < nb ? start[lane] : 0;
-            const int incl = wave_inclusive_scan(v, lane);
-            if (lane < nb) {
-                start[lane] = incl - v;
-                ptr[lane] = incl - v;
-            }
-            if (lane == 63) {
-                ptr[nb] = incl;
-                if (wave == 0) *nnzb_out = incl;
-            }
-        }
-        __syncthreads();
-    } else {
+    {
         int total = 0;
         int cnt = tid < nb ? line_start[tid] : 0;   // nb <= 1024 == kFinishThreads
         int start = block_exclusive_scan(cnt, &total, scan_scratch);
@@ -622,34 +789,40 @@ __global__ __launch_bounds__(1024) void index_check_kernel(
 // ------------------------------------------------------------------------------------------------
 // host launchers
 // ------------------------------------------------------------------------------------------------
-hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* pool, hipStream_t st) {
+hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* part, hipStream_t st) {
     const int nb = L / bs;
-    const size_t n = (size_t)nb * nb;
-    zero_u64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(
-        reinterpret_cast<unsigned long long*>(pool), n);
-    unsigned long long* out = reinterpret_cast<unsigned long long*>(pool);
-    // SPION_CONV_WGS_PER_CU workgroups per compute unit (256 of them), each walking several input blocks
-    const unsigned cap = kConvGrid, blocks = (unsigned)n;
+    const unsigned blocks = (unsigned)nb * (unsigned)nb;
+    // SPION_CONV_WAVES_PER_CU waves per compute unit (256 of them) at block 64, each walking several
+    // input blocks; smaller blocks are fewer bytes per wave, so proportionally more waves
+    auto grid = [&](unsigned waves_per_cu) {
+        const unsigned wgs = (blocks + 3) / 4, cap = 256u * waves_per_cu / 4;
+        return dim3(wgs < cap ? wgs : cap);
+    };
     if (bs == 16)
-        conv_pool_kernel<16><<<dim3(blocks < 4 * cap ? blocks : 4 * cap), dim3(64), 0, st>>>(A, L, p, out);
+        conv_pool_kernel<16><<<grid(4 * SPION_CONV_WAVES_PER_CU), dim3(256), 0, st>>>(A, L, p, part);
     else if (bs == 32)
-        conv_pool_kernel<32><<<dim3(blocks < cap ? blocks : cap), dim3(256), 0, st>>>(A, L, p, out);
+        conv_pool_kernel<32><<<grid(2 * SPION_CONV_WAVES_PER_CU), dim3(256), 0, st>>>(A, L, p, part);
     else
-        conv_pool_kernel<64><<<dim3(blocks < cap ? blocks : cap), dim3(256), 0, st>>>(A, L, p, out);
+        conv_pool_kernel<64><<<grid(SPION_CONV_WAVES_PER_CU), dim3(256), 0, st>>>(A, L, p, part);
     return hipGetLastError();
 }
 
-hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long long k_rank, double kval,
-                                 double t_abs, int no_fill, uint8_t* mask, uint8_t* expd, int* pos,
+hipError_t launch_pool_gather(const long long* part, int nb, long long* pool, hipStream_t st) {
+    pool_gather_kernel<<<dim3((unsigned)((nb * nb + 255) / 256)), dim3(256), 0, st>>>(part, nb, pool);
+    return hipGetLastError();
+}
+
+hipError_t launch_pattern_finish(const long long* part, long long* pool, int nb, int mode, long long k_rank,
+                                 double kval, double t_abs, int no_fill, uint8_t* mask, uint8_t* expd, int* pos,
                                  uint8_t* fl, int* row_ptr, int* col_idx, int* col_ptr, int* row_idx,
                                  int* bsr_pos, int* nnzb, hipStream_t st) {
     const size_t n = (size_t)nb * nb;
-    // keep static (~19 KB) + dynamic LDS under 64 KB: the three byte arrays if 3n fits, and the
+    // keep static (~25 KB) + dynamic LDS under 64 KB: the three byte arrays if 3n fits, and the
     // position array (4n more, placed at offset 4n) if 8n fits as well
-    const int use_lds = 8 * n <= 40 * 1024 ? 2 : (3 * n <= 40 * 1024 ? 1 : 0);
+    const int use_lds = 8 * n <= 36 * 1024 ? 2 : (3 * n <= 36 * 1024 ? 1 : 0);
     const size_t dyn = use_lds == 2 ? 8 * n : (use_lds == 1 ? 3 * n : 0);
     pattern_finish_kernel<<<dim3(1), dim3(kFinishThreads), dyn, st>>>(
-        pool, nb, mode, k_rank, kval, t_abs, no_fill, use_lds, mask, expd, pos, fl, row_ptr, col_idx,
+        part, pool, nb, mode, (int)k_rank, kval, t_abs, no_fill, use_lds, mask, expd, pos, fl, row_ptr, col_idx,
         col_ptr, row_idx, bsr_pos, nnzb);
     return hipGetLastError();
 }

@@ -13,7 +13,7 @@
 // transposed mask, positions) for up to SPION_STATIC_MAX_NB^2 blocks.  Every GPU the library runs
 // on holds its own copy of this array at its own address until the process ends.  In host code the
 // name is only a handle for hipGetSymbolAddress: kernels and copies are given the resolved address.
-constexpr size_t kStaticScratchBytes = 1u << 20;
+constexpr size_t kStaticScratchBytes = 5u << 20;   // the workspace of L / block = SPION_STATIC_MAX_NB
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
@@ -48,9 +48,10 @@ bool shape_ok(int32_t L, int32_t block) {
 
 // Layout of the pattern workspace for nb*nb = n cells.
 struct PatternWs {
-    size_t pool_off, mask_off, expd_off, pos_off, total;
+    size_t part_off, pool_off, mask_off, expd_off, pos_off, total;
     explicit PatternWs(size_t n) {
-        pool_off = 0;
+        part_off = 0;                                             // one record of 8 int64 per input block
+        pool_off = part_off + align_up(8 * n * sizeof(int64_t));
         mask_off = pool_off + align_up(n * sizeof(int64_t));
         expd_off = mask_off + align_up(2 * n);   // cell bits, then the transposed final mask
         pos_off = expd_off + align_up(n);
@@ -173,11 +174,13 @@ static int pattern_impl(const float* A_s, const spion_pattern_params* p, uint8_t
     char* w = static_cast<char*>(workspace);
     long long* pool = pool_sum ? reinterpret_cast<long long*>(pool_sum)
                                : reinterpret_cast<long long*>(w + ws.pool_off);
+    long long* part = reinterpret_cast<long long*>(w + ws.part_off);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (!from_pool && spion::launch_conv_pool(A_s, p->L, bs, (p->filter - 1) / 2, pool, st) != hipSuccess)
+    if (!from_pool && spion::launch_conv_pool(A_s, p->L, bs, (p->filter - 1) / 2, part, st) != hipSuccess)
         return SPION_ERR_HIP;
-    if (pool_only) return SPION_OK;
-    if (spion::launch_pattern_finish(pool, nb, mode, k_rank, kval, t_abs,
+    if (pool_only)
+        return spion::launch_pool_gather(part, nb, pool, st) == hipSuccess ? SPION_OK : SPION_ERR_HIP;
+    if (spion::launch_pattern_finish(from_pool ? nullptr : part, pool, nb, mode, k_rank, kval, t_abs,
                                      (p->flags & SPION_PATTERN_NO_FILL) ? 1 : 0,
                                      reinterpret_cast<uint8_t*>(w + ws.mask_off),
                                      reinterpret_cast<uint8_t*>(w + ws.expd_off),

@@ -8,9 +8,13 @@
 namespace spion {
 
 // pattern_kernels.hip
-hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* pool, hipStream_t st);
-hipError_t launch_pattern_finish(const long long* pool, int nb, int mode, long long k_rank, double kval,
-                                 double t_abs, int no_fill, uint8_t* mask, uint8_t* expd, int* pos,
+// part: one record of 8 int64 per input block (nb * nb records), written by launch_conv_pool;
+// launch_pool_gather / launch_pattern_finish add them up into pool[nb * nb].  launch_pattern_finish
+// with part == nullptr starts from a given pool[].
+hipError_t launch_conv_pool(const float* A, int L, int bs, int p, long long* part, hipStream_t st);
+hipError_t launch_pool_gather(const long long* part, int nb, long long* pool, hipStream_t st);
+hipError_t launch_pattern_finish(const long long* part, long long* pool, int nb, int mode, long long k_rank,
+                                 double kval, double t_abs, int no_fill, uint8_t* mask, uint8_t* expd, int* pos,
                                  uint8_t* fl, int* row_ptr, int* col_idx, int* col_ptr, int* row_idx,
                                  int* bsr_pos, int* nnzb, hipStream_t st);
 
