@@ -180,7 +180,10 @@ int spion_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *
  *   dS = P .* (dP - delta);  dQ_I += scale * dS K_J;  dK_J += scale * dS^T Q_I.
  *   Q, K, V, O, dO, LSE  as produced by / passed to spion_attn_fwd with the same index and params.
  *   dQ, dK, dV  outputs [B, H, L, d]; overwritten (not accumulated).  Results are deterministic.
- *   col_ptr, row_idx, bsr_pos  BSC index from spion_pattern (all required).
+ *   col_ptr, row_idx, bsr_pos  BSC index from spion_pattern (all required).  The kernels walk col_ptr /
+ *             row_idx; bsr_pos is not read by them (it is what spion_index_check uses to prove that the
+ *             BSC arrays are the transpose of the BSR ones) but must be passed, so that an index cannot be
+ *             handed over without its transpose.
  */
 int spion_attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
                    const float *LSE, void *dQ, void *dK, void *dV, const int32_t *row_ptr,

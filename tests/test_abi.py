@@ -79,6 +79,9 @@ def test_argument_errors_are_reported_before_any_launch():
     even = _PatternParams(256, 16, 4, sp.SPION_T_QUANTILE, 0.5, 0, 0)
     sargs[1] = ctypes.byref(even)
     assert lib.spion_pattern_static(*sargs) == -5
+    # the built-in scratch (5 MiB) holds the workspace of the largest grid the variant accepts
+    lib.spion_pattern_workspace_bytes.restype = ctypes.c_size_t
+    assert 0 < lib.spion_pattern_workspace_bytes(256 * 64, 64) <= 5 << 20
 
     ap = _AttnParams(1, 1, 256, 64, 16, sp.SPION_F32, 0.0, 0)
     fargs = [fake] * 7 + [19, ctypes.byref(ap), none, 0, none]
