@@ -116,13 +116,13 @@ static int cmp_i64(const void *a, const void *b) {
     return (x > y) - (x < y);
 }
 
-/* Threshold t of Algorithm 4 in pool_sum units (Section 4.2: "the alpha% quantile of pool_out").
+/* Threshold t of Algorithm 4 in pool_sum units (Section 4.2 takes a quantile of the pooled map).
  *   T_QUANTILE  value = q in [0,1]: nearest-rank order statistic without interpolation,
  *               t = sorted[floor(q * (n-1))]; exact integer.
  *   T_MEAN_KSTD value = k: t = mean + k * std (population std); both sums run left to right in
  *               row-major order in fp64 on (double)pool_sum.
  *   T_ABS       value = a threshold on pool_out itself: t = value * B^2 * 2^40 in fp64.
- * An entry is "critical" iff pool_sum > t (integer compare in quantile mode, fp64 otherwise). */
+ * An entry counts as above the threshold iff pool_sum > t (integer compare in quantile mode, fp64 otherwise). */
 int oracle_threshold(const int64_t *pool_sum, int32_t nb, int32_t bs, int32_t mode, double value,
                      oracle_thresh *t) {
     if (!pool_sum || !t || nb <= 0 || bs <= 0) return ORACLE_ERR_ARG;
