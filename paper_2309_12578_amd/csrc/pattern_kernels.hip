@@ -347,11 +347,14 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     int* __restrict__ nnzb_out) {
     extern __shared__ uint8_t dyn_lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long n = (long long)nb * nb;
+    const int n = nb * nb;   // at most 2^20 cells: 32-bit index arithmetic throughout (no 64-bit divisions)
     uint8_t* mask = use_lds ? dyn_lds : mask_g;
     uint8_t* expd = use_lds ? dyn_lds + n : expd_g;
     uint8_t* mask_t = use_lds ? dyn_lds + 2 * n : mask_g + n;   // final mask, transposed (step 5)
     if (use_lds > 1) pos = reinterpret_cast<int*>(dyn_lds + 4 * n);   // 3n rounded up to a multiple of 4
+    // nb <= 64: the steps after the threshold use neither expd, mask_t nor pos; pool_sum lives there
+    // instead, so that the three neighbours of every cell are read from LDS
+    long long* const pool_s = reinterpret_cast<long long*>(dyn_lds + ((n + 7) & ~7));
     // One block of LDS, used twice: three histograms while the quantile is selected; afterwards the
     // arrays of the fill and the compaction.
     __shared__ __attribute__((aligned(16))) unsigned char sh[3 * kBins * 4];
@@ -368,28 +371,30 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     static_assert(17920 + 512 <= 3 * kBins * 4 && SPION_MAX_NB_INTERNAL * 4 == 4096, "LDS carving");
     __shared__ Thresh th;
     __shared__ int scan_scratch[kFinishWaves + 1];
+    __shared__ int sel_digit, sel_below;
     const bool small = nb <= 64;
 
     // ---- 0. pool_sum from the partial records; up to kCached cells per thread stay in registers ----
     constexpr int kCached = 4;
-    const bool cached = n <= (long long)kCached * kFinishThreads;
+    const bool cached = n <= kCached * kFinishThreads;
     long long val[kCached] = {0, 0, 0, 0};
     if (part) {
-        for (long long base = 0; base < n; base += (long long)kCached * kFinishThreads) {
+        for (int base = 0; base < n; base += kCached * kFinishThreads) {
             // all records of this round are requested before the first is used
             PoolRecord rec[kCached];
 #pragma unroll
             for (int j = 0; j < kCached; ++j) {
-                const long long i = base + (long long)j * kFinishThreads + tid;
+                const int i = base + j * kFinishThreads + tid;
                 rec[j] = load_record(part, (size_t)(i < n ? i : n - 1));
             }
 #pragma unroll
             for (int j = 0; j < kCached; ++j) {
-                const long long i = base + (long long)j * kFinishThreads + tid;
+                const int i = base + j * kFinishThreads + tid;
                 if (i < n) {
-                    const long long v = sum_record(rec[j], nb, (int)(i / nb), (int)(i % nb));
+                    const long long v = sum_record(rec[j], nb, i / nb, i % nb);
                     pool[i] = v;
                     val[j] = v;
+                    if (small) pool_s[i] = v;
                 }
             }
         }
@@ -397,24 +402,27 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     } else if (cached) {
 #pragma unroll
         for (int j = 0; j < kCached; ++j) {
-            const long long i = (long long)j * kFinishThreads + tid;
-            if (i < n) val[j] = pool[i];
+            const int i = j * kFinishThreads + tid;
+            if (i < n) {
+                val[j] = pool[i];
+                if (small) pool_s[i] = val[j];
+            }
         }
     }
 
     // ---- 1. threshold ------------------------------------------------------------------------
     if (mode == 1) {
         // Exact k-th smallest (0-based) by radix selection on key = value with the sign bit flipped.
-        // One barrier per pass: after it every wave scans the histogram itself (32 bins per lane)
-        // and derives the same digit, so nothing is broadcast through LDS; three histograms rotate,
-        // the one of the pass before is cleared while the current one is scanned.
+        // A pass: every wave counts its keys' digits into a histogram; one wave scans it (32 bins per
+        // lane, a DPP prefix sum) and publishes the digit that holds rank k; three histograms rotate,
+        // the other waves clear the one of the pass before meanwhile.
         for (int i = tid; i < 3 * kBins; i += kFinishThreads) hist[i] = 0u;
         unsigned long long key[kCached];
         bool alive[kCached];   // still equal to the selected prefix
 #pragma unroll
         for (int j = 0; j < kCached; ++j) {
             key[j] = (unsigned long long)val[j] ^ 0x8000000000000000ull;
-            alive[j] = cached && (long long)j * kFinishThreads + tid < n;
+            alive[j] = cached && j * kFinishThreads + tid < n;
         }
         __syncthreads();
         unsigned long long prefix = 0ull;
@@ -440,48 +448,55 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
 #pragma unroll
                 for (int j = 0; j < kCached; ++j) count(key[j], alive[j]);
             } else {
-                for (long long base = 0; base < n; base += kFinishThreads) {
-                    const long long i = base + tid;
+                for (int base = 0; base < n; base += kFinishThreads) {
+                    const int i = base + tid;
                     const unsigned long long u =
                         i < n ? ((unsigned long long)pool[i] ^ 0x8000000000000000ull) : 0ull;
                     count(u, i < n && (top >= 64 || (u >> top) == (prefix >> top)));
                 }
             }
             __syncthreads();
-            {
-                unsigned* const hz = hist + ((pass + 2) % 3) * kBins;   // last read before the barrier above
-                for (int i = tid; i < kBins; i += kFinishThreads) hz[i] = 0u;
-            }
-            // the digit whose bin holds rank k: lane owns digits 32 lane .. 32 lane + 31 as 8 groups of 4
-            const uint4* const h4 = reinterpret_cast<const uint4*>(h);
-            int s4[8], s32 = 0;
+            if (wave != 0) {
+                // the histogram of the pass before (last read before the barrier above) is cleared for the
+                // pass after the next, off the path of the wave that scans
+                unsigned* const hz = hist + ((pass + 2) % 3) * kBins;
+                for (int i = tid - 64; i < kBins; i += kFinishThreads - 64) hz[i] = 0u;
+            } else {
+                // the digit whose bin holds rank k: lane owns digits 32 lane .. 32 lane + 31 as 8 groups of 4
+                const uint4* const h4 = reinterpret_cast<const uint4*>(h);
+                int s4[8], s32 = 0;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint4 v = h4[j * 64 + lane];
-                s4[j] = (int)(v.x + v.y + v.z + v.w);
-                s32 += s4[j];
-            }
-            const int incl = wave_inclusive_scan_dpp(s32);
-            int e = incl - s32, qj = 0;
-            const bool hit = k >= e && k < incl;   // exactly one lane: the matching keys number more than k
+                for (int j = 0; j < 8; ++j) {
+                    const uint4 v = h4[j * 64 + lane];
+                    s4[j] = (int)(v.x + v.y + v.z + v.w);
+                    s32 += s4[j];
+                }
+                const int incl = wave_inclusive_scan_dpp(s32);
+                int e = incl - s32, qj = 0;
+                const bool hit = k >= e && k < incl;   // exactly one lane: the matching keys number more than k
 #pragma unroll
-            for (int j = 0; j < 7; ++j) {
-                const bool adv = qj == j && k >= e + s4[j];
-                e = adv ? e + s4[j] : e;
-                qj = adv ? j + 1 : qj;
-            }
-            const uint4 v = h4[qj * 64 + lane];
-            const int c3[3] = {(int)v.x, (int)v.y, (int)v.z};
-            int qt = 0;
+                for (int j = 0; j < 7; ++j) {
+                    const bool adv = qj == j && k >= e + s4[j];
+                    e = adv ? e + s4[j] : e;
+                    qj = adv ? j + 1 : qj;
+                }
+                const uint4 v = h4[qj * 64 + lane];
+                const int c3[3] = {(int)v.x, (int)v.y, (int)v.z};
+                int qt = 0;
 #pragma unroll
-            for (int j = 0; j < 3; ++j) {
-                const bool adv = qt == j && k >= e + c3[j];
-                e = adv ? e + c3[j] : e;
-                qt = adv ? j + 1 : qt;
+                for (int j = 0; j < 3; ++j) {
+                    const bool adv = qt == j && k >= e + c3[j];
+                    e = adv ? e + c3[j] : e;
+                    qt = adv ? j + 1 : qt;
+                }
+                if (hit) {
+                    sel_digit = 32 * lane + 4 * qj + qt;
+                    sel_below = e;   // matching keys below that digit
+                }
             }
-            const int src = __ffsll((long long)__ballot(hit)) - 1;
-            const unsigned digit = (unsigned)__builtin_amdgcn_readlane(32 * lane + 4 * qj + qt, src);
-            k -= __builtin_amdgcn_readlane(e, src);
+            __syncthreads();
+            const unsigned digit = (unsigned)sel_digit;
+            k -= sel_below;
             prefix |= (unsigned long long)digit << shift;
 #pragma unroll
             for (int j = 0; j < kCached; ++j)
@@ -496,10 +511,10 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
         // sequential fp64 sums in row-major order: this is the definition, not an optimisation target
         if (tid == 0) {
             double sum = 0.0;
-            for (long long i = 0; i < n; ++i) sum = sum + (double)pool[i];
+            for (int i = 0; i < n; ++i) sum = sum + (double)pool[i];
             const double mean = sum / (double)n;
             double ss = 0.0;
-            for (long long i = 0; i < n; ++i) {
+            for (int i = 0; i < n; ++i) {
                 const double dlt = (double)pool[i] - mean;
                 const double sq = dlt * dlt;
                 ss = ss + sq;
@@ -528,16 +543,25 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
 
     // ---- 2. per cell: successor bits (which of down / right / diag equal their maximum), the
     //         "above threshold" bit, and the seed flag (first row and first column) ------------------
-    for (long long base = 0; base < n; base += (long long)kCached * kFinishThreads) {
+    for (int base = 0; base < n; base += kCached * kFinishThreads) {
 #pragma unroll
         for (int j = 0; j < kCached; ++j) {
-            const long long i = base + (long long)j * kFinishThreads + tid;
+            const int i = base + j * kFinishThreads + tid;
             if (i >= n) continue;
-            const int r = (int)(i / nb), c = (int)(i % nb);
+            const int r = i / nb, c = i % nb;
             const long long x = cached ? val[j] : pool[i];
             unsigned m = above(x, t) ? kAbove : 0u;
             if (r + 1 < nb && c + 1 < nb) {
-                const long long dn = pool[i + nb], rt = pool[i + 1], dg = pool[i + nb + 1];
+                long long dn, rt, dg;
+                if (small) {
+                    dn = pool_s[i + nb];
+                    rt = pool_s[i + 1];
+                    dg = pool_s[i + nb + 1];
+                } else {
+                    dn = pool[i + nb];
+                    rt = pool[i + 1];
+                    dg = pool[i + nb + 1];
+                }
                 long long mx = dn > rt ? dn : rt;
                 mx = mx > dg ? mx : dg;
                 m |= (dn == mx ? kDown : 0u) | (rt == mx ? kRight : 0u) | (dg == mx ? kDiag : 0u);
@@ -591,7 +615,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
             for (int s = 1; s <= 2 * nb - 2; ++s) {
                 const int r = tid, c = s - tid;
                 if (r < nb && c >= 0 && c < nb) {
-                    const long long i = (long long)r * nb + c;
+                    const int i = r * nb + c;
                     bool reached = false;
                     if (r >= 1) reached |= (expd[i - nb] & kExpanded) && (mask[i - nb] & kDown);
                     if (c >= 1) reached |= (expd[i - 1] & kExpanded) && (mask[i - 1] & kRight);
@@ -663,8 +687,8 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     }
 
     // ---- 4. fl_out = reached and above the threshold, or on the diagonal; kept in expd for step 5 ---
-    for (long long i = tid; i < n; i += kFinishThreads) {
-        const int r = (int)(i / nb), c = (int)(i % nb);
+    for (int i = tid; i < n; i += kFinishThreads) {
+        const int r = i / nb, c = i % nb;
         const bool reached = (expd[i] & kReached) != 0;
         const uint8_t f = ((reached && (mask[i] & kAbove)) || r == c) ? 1 : 0;
         fl[i] = f;
@@ -820,7 +844,8 @@ hipError_t launch_pattern_finish(const long long* part, long long* pool, int nb,
     // keep static (~25 KB) + dynamic LDS under 64 KB: the three byte arrays if 3n fits, and the
     // position array (4n more, placed at offset 4n) if 8n fits as well
     const int use_lds = 8 * n <= 36 * 1024 ? 2 : (3 * n <= 36 * 1024 ? 1 : 0);
-    const size_t dyn = use_lds == 2 ? 8 * n : (use_lds == 1 ? 3 * n : 0);
+    // nb <= 64: the byte map and, 8-byte aligned behind it, pool_sum itself (36 KB at nb = 64)
+    const size_t dyn = nb <= 64 ? ((n + 7) & ~(size_t)7) + 8 * n : (use_lds == 2 ? 8 * n : (use_lds == 1 ? 3 * n : 0));
     pattern_finish_kernel<<<dim3(1), dim3(kFinishThreads), dyn, st>>>(
         part, pool, nb, mode, (int)k_rank, kval, t_abs, no_fill, use_lds, mask, expd, pos, fl, row_ptr, col_idx,
         col_ptr, row_idx, bsr_pos, nnzb);
