@@ -371,7 +371,8 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     static_assert(17920 + 512 <= 3 * kBins * 4 && SPION_MAX_NB_INTERNAL * 4 == 4096, "LDS carving");
     __shared__ Thresh th;
     __shared__ int scan_scratch[kFinishWaves + 1];
-    __shared__ int sel_digit, sel_below;
+    __shared__ int sel_digit, sel_below, sel_count, cand_n;
+    __shared__ unsigned long long cand[64], sel_key;
     const bool small = nb <= 64;
 
     // ---- 0. pool_sum from the partial records; up to kCached cells per thread stay in registers ----
@@ -417,6 +418,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
         // lane, a DPP prefix sum) and publishes the digit that holds rank k; three histograms rotate,
         // the other waves clear the one of the pass before meanwhile.
         for (int i = tid; i < 3 * kBins; i += kFinishThreads) hist[i] = 0u;
+        if (tid == 0) cand_n = 0;
         unsigned long long key[kCached];
         bool alive[kCached];   // still equal to the selected prefix
 #pragma unroll
@@ -492,6 +494,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
                 if (hit) {
                     sel_digit = 32 * lane + 4 * qj + qt;
                     sel_below = e;   // matching keys below that digit
+                    sel_count = (int)(qt == 0 ? v.x : (qt == 1 ? v.y : (qt == 2 ? v.z : v.w)));   // matching keys with that digit
                 }
             }
             __syncthreads();
@@ -501,6 +504,38 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
 #pragma unroll
             for (int j = 0; j < kCached; ++j)
                 alive[j] = alive[j] && ((unsigned)(key[j] >> shift) & (unsigned)(kBins - 1)) == digit;
+            if (pass + 1 < kSelPasses && sel_count <= 64) {
+                // Few keys are left (typically after the third pass): instead of the remaining passes they
+                // are collected and one wave ranks them against each other.  k is the rank among them.
+                if (cached) {
+#pragma unroll
+                    for (int j = 0; j < kCached; ++j)
+                        if (alive[j]) cand[atomicAdd(&cand_n, 1)] = key[j];
+                } else {
+                    for (int base = 0; base < n; base += kFinishThreads) {
+                        const int i = base + tid;
+                        if (i < n) {
+                            const unsigned long long u = (unsigned long long)pool[i] ^ 0x8000000000000000ull;
+                            if ((u >> shift) == (prefix >> shift)) cand[atomicAdd(&cand_n, 1)] = u;
+                        }
+                    }
+                }
+                __syncthreads();
+                if (wave == 0) {
+                    const int cn = cand_n;   // == sel_count
+                    const unsigned long long mine = lane < cn ? cand[lane] : ~0ull;
+                    int less = 0, same = 0;
+                    for (int t = 0; t < cn; ++t) {
+                        const unsigned long long other = cand[t];
+                        less += other < mine ? 1 : 0;
+                        same += other == mine ? 1 : 0;
+                    }
+                    if (lane < cn && k >= less && k < less + same) sel_key = mine;   // equal keys write the same value
+                }
+                __syncthreads();
+                prefix = sel_key;
+                break;
+            }
         }
         if (tid == 0) {
             th.is_int = 1;
