@@ -218,14 +218,16 @@ __device__ __forceinline__ PoolRecord load_record(const long long* __restrict__ 
     return rec;
 }
 __device__ __forceinline__ long long sum_record(const PoolRecord& rec, int nb, int ti, int tj) {
+    // slot s was written by input block (ti - di(s), tj - dj(s)): it exists iff the pooled block has a
+    // neighbour on that side
+    const bool up = ti >= 1, down = ti + 1 < nb, left = tj >= 1, right = tj + 1 < nb;
+    const bool ok[7] = {true, down, up, right, left, down && right, up && left};
     long long acc = 0;
 #pragma unroll
     for (int s = 0; s < 7; ++s) {
         const uint4 q = rec.q[s >> 1];
         const unsigned long long v = (s & 1) ? ((unsigned long long)q.w << 32 | q.z) : ((unsigned long long)q.y << 32 | q.x);
-        const int si = ti - slot_di(s), sj = tj - slot_dj(s);
-        const bool ok = si >= 0 && si < nb && sj >= 0 && sj < nb;
-        acc += ok ? (long long)v : 0ll;
+        acc += ok[s] ? (long long)v : 0ll;
     }
     return acc;
 }
@@ -251,10 +253,6 @@ struct Thresh {
     long long ti;
     double td;
 };
-
-__device__ __forceinline__ bool above(long long x, const Thresh& t) {
-    return t.is_int ? (x > t.ti) : ((double)x > t.td);
-}
 
 __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
 #pragma unroll
@@ -375,38 +373,60 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     __shared__ unsigned long long cand[64], sel_key;
     const bool small = nb <= 64;
 
-    // ---- 0. pool_sum from the partial records; up to kCached cells per thread stay in registers ----
+    // ---- 0. pool_sum from the partial records.  nb <= 64: thread (wave, lane) owns the cells
+    //         (wave + 16 j, lane), j < 4, and keeps their values in registers (no division is needed to
+    //         find a cell's row and column); larger grids walk the cells with a stride ------------------
     constexpr int kCached = 4;
-    const bool cached = n <= kCached * kFinishThreads;
+    static_assert(kCached * kFinishWaves == 64, "the owned cells of a thread cover 64 rows");
+    auto own_cell = [&](int j, int& i) {
+        const int r = wave + kFinishWaves * j;
+        i = r * nb + lane;
+        return r < nb && lane < nb;
+    };
     long long val[kCached] = {0, 0, 0, 0};
     if (part) {
-        for (int base = 0; base < n; base += kCached * kFinishThreads) {
-            // all records of this round are requested before the first is used
+        if (small) {
+            // all records are requested before the first is used
             PoolRecord rec[kCached];
 #pragma unroll
             for (int j = 0; j < kCached; ++j) {
-                const int i = base + j * kFinishThreads + tid;
-                rec[j] = load_record(part, (size_t)(i < n ? i : n - 1));
+                int i;
+                const bool ok = own_cell(j, i);
+                rec[j] = load_record(part, (size_t)(ok ? i : 0));
             }
 #pragma unroll
             for (int j = 0; j < kCached; ++j) {
-                const int i = base + j * kFinishThreads + tid;
-                if (i < n) {
-                    const long long v = sum_record(rec[j], nb, i / nb, i % nb);
+                int i;
+                if (own_cell(j, i)) {
+                    const long long v = sum_record(rec[j], nb, wave + kFinishWaves * j, lane);
                     pool[i] = v;
                     val[j] = v;
-                    if (small) pool_s[i] = v;
+                    pool_s[i] = v;
+                }
+            }
+        } else {
+            for (int base = 0; base < n; base += kCached * kFinishThreads) {
+                PoolRecord rec[kCached];
+#pragma unroll
+                for (int j = 0; j < kCached; ++j) {
+                    const int i = base + j * kFinishThreads + tid;
+                    rec[j] = load_record(part, (size_t)(i < n ? i : n - 1));
+                }
+#pragma unroll
+                for (int j = 0; j < kCached; ++j) {
+                    const int i = base + j * kFinishThreads + tid;
+                    if (i < n) pool[i] = sum_record(rec[j], nb, i / nb, i % nb);
                 }
             }
         }
         __syncthreads();   // pool[] is read by other threads from here on
-    } else if (cached) {
+    } else if (small) {
 #pragma unroll
         for (int j = 0; j < kCached; ++j) {
-            const int i = j * kFinishThreads + tid;
-            if (i < n) {
+            int i;
+            if (own_cell(j, i)) {
                 val[j] = pool[i];
-                if (small) pool_s[i] = val[j];
+                pool_s[i] = val[j];
             }
         }
     }
@@ -424,7 +444,8 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
 #pragma unroll
         for (int j = 0; j < kCached; ++j) {
             key[j] = (unsigned long long)val[j] ^ 0x8000000000000000ull;
-            alive[j] = cached && j * kFinishThreads + tid < n;
+            int i;
+            alive[j] = small && own_cell(j, i);
         }
         __syncthreads();
         unsigned long long prefix = 0ull;
@@ -446,7 +467,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
                     atomicAdd(&h[bin_slot(digit)], 1u);
                 }
             };
-            if (cached) {
+            if (small) {
 #pragma unroll
                 for (int j = 0; j < kCached; ++j) count(key[j], alive[j]);
             } else {
@@ -507,7 +528,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
             if (pass + 1 < kSelPasses && sel_count <= 64) {
                 // Few keys are left (typically after the third pass): instead of the remaining passes they
                 // are collected and one wave ranks them against each other.  k is the rank among them.
-                if (cached) {
+                if (small) {
 #pragma unroll
                     for (int j = 0; j < kCached; ++j)
                         if (alive[j]) cand[atomicAdd(&cand_n, 1)] = key[j];
@@ -578,32 +599,47 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
 
     // ---- 2. per cell: successor bits (which of down / right / diag equal their maximum), the
     //         "above threshold" bit, and the seed flag (first row and first column) ------------------
-    for (int base = 0; base < n; base += kCached * kFinishThreads) {
+    auto cell_bits = [&](long long x, long long dn, long long rt, long long dg, bool inner) {
+        bool ab;
+        if (t.is_int) ab = x > t.ti;
+        else ab = (double)x > t.td;
+        unsigned m = ab ? kAbove : 0u;
+        if (inner) {
+            long long mx = dn > rt ? dn : rt;
+            mx = mx > dg ? mx : dg;
+            m |= (dn == mx ? kDown : 0u) | (rt == mx ? kRight : 0u) | (dg == mx ? kDiag : 0u);
+        }
+        return m;
+    };
+    if (small) {
 #pragma unroll
         for (int j = 0; j < kCached; ++j) {
-            const int i = base + j * kFinishThreads + tid;
-            if (i >= n) continue;
-            const int r = i / nb, c = i % nb;
-            const long long x = cached ? val[j] : pool[i];
-            unsigned m = above(x, t) ? kAbove : 0u;
-            if (r + 1 < nb && c + 1 < nb) {
-                long long dn, rt, dg;
-                if (small) {
-                    dn = pool_s[i + nb];
-                    rt = pool_s[i + 1];
-                    dg = pool_s[i + nb + 1];
-                } else {
-                    dn = pool[i + nb];
-                    rt = pool[i + 1];
-                    dg = pool[i + nb + 1];
-                }
-                long long mx = dn > rt ? dn : rt;
-                mx = mx > dg ? mx : dg;
-                m |= (dn == mx ? kDown : 0u) | (rt == mx ? kRight : 0u) | (dg == mx ? kDiag : 0u);
+            int i;
+            if (!own_cell(j, i)) continue;
+            const int r = wave + kFinishWaves * j, c = lane;
+            const bool inner = r + 1 < nb && c + 1 < nb;
+            long long dn = 0, rt = 0, dg = 0;
+            if (inner) {
+                dn = pool_s[i + nb];
+                rt = pool_s[i + 1];
+                dg = pool_s[i + nb + 1];
             }
+            const unsigned m = cell_bits(val[j], dn, rt, dg, inner);
             mask[i] = (uint8_t)m;
-            if (small) skew[r * 128 + r + c] = (uint8_t)(m & 7u);
-            else expd[i] = no_fill ? (uint8_t)kReached : ((r == 0 || c == 0) ? (uint8_t)kExpanded : (uint8_t)0);
+            skew[r * 128 + r + c] = (uint8_t)(m & 7u);
+        }
+    } else {
+        for (int i = tid; i < n; i += kFinishThreads) {
+            const int r = i / nb, c = i % nb;
+            const bool inner = r + 1 < nb && c + 1 < nb;
+            long long dn = 0, rt = 0, dg = 0;
+            if (inner) {
+                dn = pool[i + nb];
+                rt = pool[i + 1];
+                dg = pool[i + nb + 1];
+            }
+            mask[i] = (uint8_t)cell_bits(pool[i], dn, rt, dg, inner);
+            expd[i] = no_fill ? (uint8_t)kReached : ((r == 0 || c == 0) ? (uint8_t)kExpanded : (uint8_t)0);
         }
     }
     __syncthreads();
