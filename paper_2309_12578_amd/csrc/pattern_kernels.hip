@@ -717,9 +717,19 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
             if (lane == 0) rowmask[r] = m;
         }
         __syncthreads();
+        {
+            // the column words: lane r holds row r's word, a ballot over bit c is column c; wave w makes the
+            // columns w, w + 16, ...
+            const unsigned long long rm = lane < nb ? rowmask[lane] : 0ull;
+            for (int c = wave; c < nb; c += kFinishWaves) {
+                const unsigned long long cm = __ballot(((rm >> c) & 1ull) != 0ull);
+                if (lane == 0) colmask[c] = cm;
+            }
+        }
+        __syncthreads();
         if (wave == 0) {
             const int v = lane < nb ? __popcll(rowmask[lane]) : 0;
-            const int incl = wave_inclusive_scan(v, lane);
+            const int incl = wave_inclusive_scan_dpp(v);
             if (lane < nb) {
                 line_start[lane] = incl - v;
                 row_ptr[lane] = incl - v;
@@ -729,11 +739,8 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
                 *nnzb_out = incl;
             }
         } else if (wave == 1 && want_bsc) {
-            unsigned long long cm = 0ull;
-            for (int r = 0; r < nb; ++r) cm |= ((rowmask[r] >> lane) & 1ull) << r;
-            if (lane < nb) colmask[lane] = cm;
-            const int v = lane < nb ? __popcll(cm) : 0;
-            const int incl = wave_inclusive_scan(v, lane);
+            const int v = lane < nb ? __popcll(colmask[lane]) : 0;
+            const int incl = wave_inclusive_scan_dpp(v);
             if (lane < nb) {
                 col_start[lane] = incl - v;
                 col_ptr[lane] = incl - v;
