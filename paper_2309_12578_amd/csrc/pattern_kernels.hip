@@ -92,8 +92,13 @@ __global__ __launch_bounds__(256, BS == 64 ? 2 : 4) void conv_pool_kernel(const 
         }
     };
 
-    long long tot[8];
-    long long s_all;
+    // Per lane and block the sums stay in fp64: every term is an integer (a quantised score below 2^41
+    // in magnitude times a weight below 2^7), at most 64 of them go into one sum, so every partial sum
+    // is an integer below 2^53 and the fp64 additions are exact.  (fp64 adds and fused multiply-adds
+    // issue at the rate of fp32 ones here; the same sums in 64-bit integer arithmetic take three to
+    // four instructions per term.)
+    double tot[8];
+    double s_all;
     // sub-tiles [half * HS, half * HS + HS) of the current block, scores in src
     auto work_half = [&](int half, const float4 (&src)[HS]) {
         // The edge weights and the coordinates they are made from depend only on the lane, the sub-tile
@@ -114,31 +119,21 @@ __global__ __launch_bounds__(256, BS == 64 ? 2 : 4) void conv_pool_kernel(const 
             const int r0_lo = (u - BS + 1) > -p ? (u - BS + 1) : -p, r0_hi = u < p ? u : p;
             const int rp_lo = -p, rp_hi = u - BS;
             const float av[4] = {src[k].x, src[k].y, src[k].z, src[k].w};
-            int hi[4], lo[4], c0_lo[4], c0_hi[4];
-            int s_hi = 0, s_lo = 0;
+            double q[4];   // a_q = rint(a * 2^40), ties to even: an integer, exact in fp64
+            int c0_lo[4], c0_hi[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int v = v0 + e;
-                const float x = av[e] * 1048576.0f;
-                const float xf = floorf(x);
-                hi[e] = (int)xf;
-                lo[e] = (int)rintf((x - xf) * 1048576.0f);
-                s_hi += hi[e];
-                s_lo += lo[e];
+                q[e] = __builtin_rint((double)av[e] * 1099511627776.0);
                 c0_lo[e] = (v - BS + 1) > -p ? (v - BS + 1) : -p;
                 c0_hi[e] = v < p ? v : p;
             }
-            s_all += ((long long)s_hi << 20) + s_lo;
-            // weights < 128 and |hi|, lo <= 2^20: 24-bit multiplies, 4 terms fit 32 bits
+            s_all += (q[0] + q[1]) + (q[2] + q[3]);
             auto edge = [&](int slot, auto weight) {
-                int n_hi = 0, n_lo = 0;
+                double acc = tot[slot];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int w = weight(e);
-                    n_hi += __mul24(w, hi[e]);
-                    n_lo += __mul24(w, lo[e]);
-                }
-                tot[slot] += ((long long)n_hi << 20) + n_lo;
+                for (int e = 0; e < 4; ++e) acc = __builtin_fma((double)weight(e), q[e], acc);
+                tot[slot] = acc;
             };
             if (top) edge(1, [&](int e) { return isect(rm_lo, rm_hi, c0_lo[e], c0_hi[e]); });
             if (bottom) edge(2, [&](int e) { return isect(rp_lo, rp_hi, c0_lo[e], c0_hi[e]); });
@@ -154,8 +149,8 @@ __global__ __launch_bounds__(256, BS == 64 ? 2 : 4) void conv_pool_kernel(const 
     for (int blk = first; blk < n_blocks; blk += n_waves) {
         const bool more = blk + n_waves < n_blocks;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) tot[t] = 0;
-        s_all = 0;
+        for (int t = 0; t < 8; ++t) tot[t] = 0.0;
+        s_all = 0.0;
         if constexpr (NH == 2) {
             load_half(blk, 1, b);
             work_half(0, a);
@@ -167,33 +162,39 @@ __global__ __launch_bounds__(256, BS == 64 ? 2 : 4) void conv_pool_kernel(const 
 #pragma unroll
             for (int k = 0; k < HS; ++k) a[k] = b[k];
         }
+        // from here on in 64-bit integers: the sums over the wave's lanes can exceed 2^53
+        long long ti64[8];
         long long others = 0;
 #pragma unroll
-        for (int t = 1; t < 7; ++t) others += tot[t];
-        tot[0] = (long long)(2 * p_arg + 1) * s_all - others;
+        for (int t = 1; t < 7; ++t) {
+            ti64[t] = (long long)tot[t];
+            others += ti64[t];
+        }
+        ti64[0] = (long long)(2 * p_arg + 1) * (long long)s_all - others;
+        ti64[7] = 0;
 
         // reduce-scatter butterfly over the wave: 8 slots -> 4 -> 2 -> 1, then 3 plain steps
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const bool up = lane & 32;
-            const long long send = up ? tot[k] : tot[k + 4];
-            const long long keep = up ? tot[k + 4] : tot[k];
-            tot[k] = keep + shfl_xor_i64(send, 32);
+            const long long send = up ? ti64[k] : ti64[k + 4];
+            const long long keep = up ? ti64[k + 4] : ti64[k];
+            ti64[k] = keep + shfl_xor_i64(send, 32);
         }
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const bool up = lane & 16;
-            const long long send = up ? tot[k] : tot[k + 2];
-            const long long keep = up ? tot[k + 2] : tot[k];
-            tot[k] = keep + shfl_xor_i64(send, 16);
+            const long long send = up ? ti64[k] : ti64[k + 2];
+            const long long keep = up ? ti64[k + 2] : ti64[k];
+            ti64[k] = keep + shfl_xor_i64(send, 16);
         }
         {
             const bool up = lane & 8;
-            const long long send = up ? tot[0] : tot[1];
-            const long long keep = up ? tot[1] : tot[0];
-            tot[0] = keep + shfl_xor_i64(send, 8);
+            const long long send = up ? ti64[0] : ti64[1];
+            const long long keep = up ? ti64[1] : ti64[0];
+            ti64[0] = keep + shfl_xor_i64(send, 8);
         }
-        long long s = tot[0];
+        long long s = ti64[0];
         s += shfl_xor_i64(s, 4);
         s += shfl_xor_i64(s, 2);
         s += shfl_xor_i64(s, 1);
