@@ -38,10 +38,11 @@ namespace spion {
 // Fixed point without 64-bit arithmetic in the inner loop: for |a| <= 1, x = a * 2^20 is exact in
 // fp32, hi = floor(x), lo = rint((x - hi) * 2^20) are exact integers of at most 21 bits and
 // a_q = hi * 2^20 + lo == rint(a * 2^40) with ties to even.
-// Build-time tunable of conv_pool_kernel: waves per compute unit (256 of them).  Measured at L = 4096,
-// block 64 (cold map): 8 and 16 measure alike, 12 is 6 % and 4 is 12 % slower.
+// Build-time tunable of conv_pool_kernel: waves launched per compute unit (256 of them) at block 64; two
+// per SIMD are resident.  Measured at L = 4096, block 64 (cold map, whole call): 16 (every wave one
+// block) 45.0 us, 8 46.9 us, 4 49.5 us.
 #ifndef SPION_CONV_WAVES_PER_CU
-#define SPION_CONV_WAVES_PER_CU 8
+#define SPION_CONV_WAVES_PER_CU 16
 #endif
 
 __device__ __forceinline__ int isect(int lo_a, int hi_a, int lo_b, int hi_b) {
