@@ -133,6 +133,21 @@ def test_pattern_plateau_map_and_tiny_values(sp):
     _check_pattern(sp, A, block, 3, si.T_QUANTILE, 0.5)
 
 
+@pytest.mark.parametrize("L,block,filt", [(256, 16, 7), (1024, 32, 31), (4096, 64, 31), (1024, 64, 127)])
+def test_pattern_signed_scores(sp, L, block, filt):
+    """Scores of both signs (the interface allows |a| <= 1): negative fixed-point values in the
+    convolution, pooled sums on both sides of zero in the order statistic and in the fp64 threshold."""
+    rng = np.random.default_rng(L + block)
+    A = rng.uniform(-1.0, 1.0, size=(L, L)).astype(np.float32)
+    A[rng.random((L, L)) < 0.3] *= 2.0 ** -20           # values that need the low fixed-point bits
+    i = np.arange(L)
+    A[i, (i * 7) % L] = -1.0
+    A[(i * 5) % L, i] = 1.0
+    _check_pattern(sp, A, block, filt, si.T_QUANTILE, 0.6)
+    _check_pattern(sp, A, block, filt, si.T_MEAN_KSTD, 0.25)
+    _check_pattern(sp, A, block, filt, si.T_ABS, -0.001)
+
+
 def test_pattern_variants_no_fill_and_no_conv(sp):
     w = si.workload(1)
     Q, K, _, _ = si.make_qkv_do(w)
