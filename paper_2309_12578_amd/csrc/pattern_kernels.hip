@@ -282,6 +282,21 @@ __device__ __forceinline__ int wave_inclusive_scan_dpp(int v) {
     return v;
 }
 
+// Minimum over the wave, same data movement; the result is in lane 63.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_fetch_or_self(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ int wave_min_dpp(int v) {
+    v = min(v, dpp_fetch_or_self<0x111, 0xf>(v));
+    v = min(v, dpp_fetch_or_self<0x112, 0xf>(v));
+    v = min(v, dpp_fetch_or_self<0x114, 0xf>(v));
+    v = min(v, dpp_fetch_or_self<0x118, 0xf>(v));
+    v = min(v, dpp_fetch_or_self<0x142, 0xa>(v));
+    v = min(v, dpp_fetch_or_self<0x143, 0xc>(v));
+    return v;
+}
+
 // Exclusive prefix sum over one value per thread.  Returns the exclusive prefix of this thread's
 // value; *total gets the sum.  All threads call.  scratch: kFinishWaves + 1 ints of LDS.
 __device__ int block_exclusive_scan(int v, int* total, int* scratch) {
@@ -371,13 +386,14 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
     static_assert(17920 + 512 <= 3 * kBins * 4 && SPION_MAX_NB_INTERNAL * 4 == 4096, "LDS carving");
     __shared__ Thresh th;
     __shared__ int scan_scratch[kFinishWaves + 1];
-    __shared__ int sel_digit, sel_below, sel_count, cand_n;
+    __shared__ int sel_digit, sel_below, sel_count, cand_n, common_lz;
     __shared__ unsigned long long cand[64], sel_key;
     const bool small = nb <= 64;
 
     // ---- 0. pool_sum from the partial records.  nb <= 64: thread (wave, lane) owns the cells
     //         (wave + 16 j, lane), j < 4, and keeps their values in registers (no division is needed to
     //         find a cell's row and column); larger grids walk the cells with a stride ------------------
+    if (tid == 0) common_lz = 64;   // (read after the barrier that ends this step)
     constexpr int kCached = 4;
     static_assert(kCached * kFinishWaves == 64, "the owned cells of a thread cover 64 rows");
     auto own_cell = [&](int j, int& i) {
@@ -431,6 +447,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
                 pool_s[i] = val[j];
             }
         }
+        __syncthreads();
     }
 
     // ---- 1. threshold ------------------------------------------------------------------------
@@ -443,19 +460,32 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
         if (tid == 0) cand_n = 0;
         unsigned long long key[kCached];
         bool alive[kCached];   // still equal to the selected prefix
+        // The leading bits that all keys share need no pass: pooled sums of scores in [0, 1] share their
+        // first 14 bits or more.  Every key is compared with the key of cell (0, 0); the smallest number
+        // of leading bits any key shares with it is what all keys share.  (nb <= 64 only.)
+        const unsigned long long ref = small ? ((unsigned long long)pool_s[0] ^ 0x8000000000000000ull) : 0ull;
+        unsigned long long differ = 0ull;
 #pragma unroll
         for (int j = 0; j < kCached; ++j) {
             key[j] = (unsigned long long)val[j] ^ 0x8000000000000000ull;
             int i;
             alive[j] = small && own_cell(j, i);
+            if (alive[j]) differ |= key[j] ^ ref;
+        }
+        if (small) {
+            const int lz = wave_min_dpp(differ ? __clzll((long long)differ) : 64);
+            if (lane == 63) atomicMin(&common_lz, lz);
         }
         __syncthreads();
+        const int shared_bits = small ? common_lz : 0;
+        const int n_passes = (64 - shared_bits + kDigitBits - 1) / kDigitBits;   // 0: all keys are equal
         unsigned long long prefix = 0ull;
+        if (small && kDigitBits * n_passes < 64) prefix = ref & ~((1ull << (kDigitBits * n_passes)) - 1ull);
         int k = k_rank;
 #pragma unroll 1
-        for (int pass = 0; pass < kSelPasses; ++pass) {
-            const int shift = kDigitBits * (kSelPasses - 1 - pass);   // 55, 44, ..., 0
-            const int top = shift + kDigitBits;                       // bits >= top are already decided
+        for (int pass = 0; pass < n_passes; ++pass) {
+            const int shift = kDigitBits * (n_passes - 1 - pass);   // without shared bits: 55, 44, ..., 0
+            const int top = shift + kDigitBits;                     // bits >= top are already decided
             unsigned* const h = hist + (pass % 3) * kBins;
             auto count = [&](unsigned long long u, bool match) {
                 const unsigned digit = (unsigned)(u >> shift) & (unsigned)(kBins - 1);
@@ -527,7 +557,7 @@ __global__ __launch_bounds__(kFinishThreads) void pattern_finish_kernel(
 #pragma unroll
             for (int j = 0; j < kCached; ++j)
                 alive[j] = alive[j] && ((unsigned)(key[j] >> shift) & (unsigned)(kBins - 1)) == digit;
-            if (pass + 1 < kSelPasses && sel_count <= 64) {
+            if (pass + 1 < n_passes && sel_count <= 64) {
                 // Few keys are left (typically after the third pass): instead of the remaining passes they
                 // are collected and one wave ranks them against each other.  k is the rank among them.
                 if (small) {
