@@ -43,10 +43,15 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
 __device__ __forceinline__ KeyItem key_item_lookup(const int* __restrict__ col_ptr, int nb, int w, int lane) {
     KeyItem none = {-1, 0, 0, -1};
     int run = 0;   // chunks of split columns in the column groups before this one
+    int c0_first = 0, cnt_first = 0;   // columns 0 .. 63, kept for the second search
     for (int base = 0; base < nb; base += 64) {
         const int J = base + lane;
         const bool valid = J < nb;
         const int c0 = valid ? col_ptr[J] : 0, cnt = valid ? col_ptr[J + 1] - c0 : 0;
+        if (base == 0) {
+            c0_first = c0;
+            cnt_first = cnt;
+        }
         const int nch = cnt > kChunk ? (cnt + kChunk - 1) / kChunk : 0;
         const int incl = wave_incl_scan(nch, lane);
         const int lo = run + incl - nch;
@@ -66,7 +71,11 @@ __device__ __forceinline__ KeyItem key_item_lookup(const int* __restrict__ col_p
     for (int base = 0; base < nb; base += 64) {
         const int J = base + lane;
         const bool valid = J < nb;
-        const int c0 = valid ? col_ptr[J] : 0, c1 = valid ? col_ptr[J + 1] : 0;
+        int c0 = c0_first, c1 = c0_first + cnt_first;
+        if (base != 0) {
+            c0 = valid ? col_ptr[J] : 0;
+            c1 = valid ? col_ptr[J + 1] : 0;
+        }
         const unsigned long long whole = __ballot(valid && c1 - c0 <= kChunk);
         const unsigned long long hit = __ballot(valid && c1 - c0 <= kChunk && lanes_below(whole) == u);
         if (hit) {

@@ -183,12 +183,21 @@ __host__ __device__ inline int key_work_items_max(int nnzb, int nb) { return nnz
 __host__ __device__ inline int key_slots_max(int nnzb) { return 2 * (nnzb / kChunk) + 2; }
 __host__ __device__ inline int key_split_max(int nnzb) { return nnzb / (kChunk + 1) + 1; }
 
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(v, off);
-        if (lane >= off) v += o;
-    }
+// Inclusive prefix sum over the wave with DPP moves (VALU speed, no LDS crossbar): shifts of 1, 2, 4, 8
+// inside each row of 16 lanes, then lane 15 of rows 0 and 2 added to rows 1 and 3, then lane 31 added
+// to rows 2 and 3.  A lane whose source is outside its row, or whose row is masked off, adds the 0
+// given as old value.  All lanes must be active.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_fetch0(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ int wave_incl_scan(int v, int /*lane*/) {
+    v += dpp_fetch0<0x111, 0xf>(v);   // row_shr:1
+    v += dpp_fetch0<0x112, 0xf>(v);   // row_shr:2
+    v += dpp_fetch0<0x114, 0xf>(v);   // row_shr:4
+    v += dpp_fetch0<0x118, 0xf>(v);   // row_shr:8
+    v += dpp_fetch0<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_fetch0<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
     return v;
 }
 
