@@ -2,8 +2,9 @@
 //
 //   conv_pool_kernel      Eq. 3 + Eq. 4 fused: one streaming pass over A^s that splits every input
 //                         block's (fixed-point) scores over the <= 7 pooled blocks its diagonal filter
-//                         window touches and writes those seven sums as one record per input block.
-//                         HBM bound: A^s is read exactly once, nothing L x L is written, no atomics.
+//                         window touches and writes each of the seven sums into a slot of the record
+//                         of the pooled block it belongs to.  HBM bound: A^s is read exactly once,
+//                         nothing L x L is written, no atomics.
 //   pattern_finish_kernel one workgroup: adds the records up into pool_sum, then threshold (exact
 //                         order statistic / mean + k std),
 //                         successor bits, anti-diagonal wavefront flood fill, forced diagonal,
@@ -35,9 +36,9 @@ namespace spion {
 // g-intervals for a local coordinate x in [0, bs): block offset -1: [x+1, p], 0: [max(x-bs+1,-p),
 // min(x,p)], +1: [-p, x-bs].
 //
-// Fixed point without 64-bit arithmetic in the inner loop: for |a| <= 1, x = a * 2^20 is exact in
-// fp32, hi = floor(x), lo = rint((x - hi) * 2^20) are exact integers of at most 21 bits and
-// a_q = hi * 2^20 + lo == rint(a * 2^40) with ties to even.
+// Fixed point in fp64: for |a| <= 1, a_q = rint((double)a * 2^40) (ties to even) is an integer of at
+// most 41 bits, exact in fp64, and so are its products with the weights (< 2^7) and the sums of up
+// to 64 of them that a lane forms per block (< 2^53); see the kernel.
 // Build-time tunable of conv_pool_kernel: waves launched per compute unit (256 of them) at block 64; two
 // per SIMD are resident.  Measured at L = 4096, block 64 (cold map, whole call): 16 (every wave one
 // block) 45.0 us, 8 46.9 us, 4 49.5 us.
