@@ -332,6 +332,26 @@ def test_attention_small_all_kernels(sp, dtype, block, density):
     print(dtype, block, density, {k: f"{v[0]:.2e}" for k, v in errs.items()})
 
 
+@pytest.mark.parametrize("block", [32, 64])
+def test_attention_more_than_64_block_columns(sp, block):
+    """96 block columns: the work-item lookup of the backward scans the column counts in two groups
+    of 64; split columns (more than 16 kept rows) sit in both groups, next to short and empty-but-for-
+    the-diagonal ones; 8 heads, so the workgroup-to-XCD mapping by head is in play."""
+    nb, BH, d = 96, 8, 64
+    L = nb * block
+    rng = np.random.default_rng(block + 96)
+    Q, K, V, dO = [si.round_to_dtype(rng.standard_normal((BH, L, d), dtype=np.float32), "bf16")
+                   for _ in range(4)]
+    fl = si.random_block_mask(nb, 0.06, seed=block + 5)
+    fl[:, 7] = 1                                  # tall columns in the first group ...
+    fl[rng.choice(nb, 40, replace=False), 33] = 1
+    fl[:, 80] = 1                                 # ... and in the second
+    fl[rng.choice(nb, 21, replace=False), 95] = 1
+    fl[:, 70] = 0
+    fl[70, 70] = 1                                # a column of one block
+    _run_attention_case(sp, Q, K, V, dO, fl, block, "bf16", heads=[0, 5, 7])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_degenerate_patterns(sp, dtype):
     block, nb, BH, d = 32, 4, 2, 64
